@@ -1,0 +1,332 @@
+/*
+ * tess_oracle.c -- CPU fp64 oracle for the per-processor compute of a linear
+ * layer partitioned over a Tesseract [q, q, d] processor grid.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  Only the test-suite, the
+ * smoke check and the benchmark's cpu_baseline leg may call it.  It shares no
+ * code, header, table or helper with the HIP library, and the HIP library
+ * never calls it.
+ *
+ * Everything is the plain definition written out in double precision:
+ * Tesseract re-brackets a dense matrix product exactly (the paper's
+ * experiment section checks the partitioned result against the unpartitioned
+ * one and its conclusion states that no approximation is introduced), so the
+ * oracle is the definition of the blocked sums, evaluated with the panels in
+ * ascending step order t = 0..q-1 and, inside a panel, the contracted index
+ * ascending.  No tiling, no fusion, no BLAS.
+ *
+ * Pinned (tests/test_oracle_pins.py) against: numpy's fp64 matmul on the
+ * unpartitioned matrices (reassembly invariant of Alg. 3, gradient identities
+ * of the SUMMA gradient equation, depth sum of Section 3.1), the adjoint
+ * identity <dY, XW> = <dX, X> = <dW, W>, one-hot inputs that expose the block
+ * map h = i + k*q, the hand-written partition table under tests/golden/,
+ * exact small-integer products, textbook values of the normal CDF for GELU,
+ * and bit-level ties for the bf16 rounding helper.
+ *
+ * Build: gcc -O2 -fopenmp -fPIC -shared -o libtess_oracle.so tess_oracle.c -lm
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_ACT_NONE 0
+#define ORC_ACT_GELU_ERF 1
+#define ORC_ACT_GELU_TANH 2
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---- scalar helpers ------------------------------------------------------ */
+
+/* GELU as x * Phi(x), Phi the standard normal CDF (the definition), and the
+ * tanh form that some frameworks use instead.  The paper only says that the
+ * MLP has an activation between its two linears (Section 2.4). */
+double orc_gelu_erf(double x) { return 0.5 * x * (1.0 + erf(x / sqrt(2.0))); }
+
+double orc_gelu_tanh(double x)
+{
+    const double pi = 3.14159265358979323846;
+    const double c = sqrt(2.0 / pi);
+    return 0.5 * x * (1.0 + tanh(c * (x + 0.044715 * x * x * x)));
+}
+
+static double orc_act(double x, int act)
+{
+    if (act == ORC_ACT_GELU_ERF) return orc_gelu_erf(x);
+    if (act == ORC_ACT_GELU_TANH) return orc_gelu_tanh(x);
+    return x;
+}
+
+/* Round an fp32 value to the nearest bfloat16 (ties to even mantissa) and
+ * return it widened back to fp32.  bfloat16 is the upper 16 bits of the
+ * IEEE-754 binary32 pattern. NaN stays NaN (quiet). */
+float orc_round_bf16_scalar(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) {
+        u = (u | 0x00400000u) & 0xffff0000u;
+    } else {
+        uint32_t lsb = (u >> 16) & 1u;
+        u += 0x7fffu + lsb;
+        u &= 0xffff0000u;
+    }
+    memcpy(&x, &u, 4);
+    return x;
+}
+
+void orc_round_bf16(const float* in, double* out, int64_t count)
+{
+    for (int64_t e = 0; e < count; ++e) out[e] = (double)orc_round_bf16_scalar(in[e]);
+}
+
+/* ---- unpartitioned definitions ------------------------------------------- */
+
+/* C[M,N] = A[M,K] * B[K,N], all row-major and packed. */
+void orc_matmul_nn(const double* A, const double* B, double* C, int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; ++r) {
+        double* crow = C + r * N;
+        for (int64_t s = 0; s < N; ++s) crow[s] = 0.0;
+        for (int64_t u = 0; u < K; ++u) {
+            const double av = A[r * K + u];
+            const double* brow = B + u * N;
+            for (int64_t s = 0; s < N; ++s) crow[s] += av * brow[s];
+        }
+    }
+}
+
+/* C[M,N] = A[M,K] * B[N,K]^T. */
+void orc_matmul_nt(const double* A, const double* B, double* C, int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; ++r) {
+        for (int64_t s = 0; s < N; ++s) {
+            double acc = 0.0;
+            for (int64_t u = 0; u < K; ++u) acc += A[r * K + u] * B[s * K + u];
+            C[r * N + s] = acc;
+        }
+    }
+}
+
+/* C[M,N] = A[K,M]^T * B[K,N]. */
+void orc_matmul_tn(const double* A, const double* B, double* C, int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; ++r) {
+        double* crow = C + r * N;
+        for (int64_t s = 0; s < N; ++s) crow[s] = 0.0;
+        for (int64_t u = 0; u < K; ++u) {
+            const double av = A[u * M + r];
+            const double* brow = B + u * N;
+            for (int64_t s = 0; s < N; ++s) crow[s] += av * brow[s];
+        }
+    }
+}
+
+/* ---- partition of Alg. 3 --------------------------------------------------
+ * A[a,b] is cut into q*d block rows and q block columns, B[b,c] into q x q
+ * blocks that every depth layer holds a copy of, C[a,c] like A.  Processor
+ * (i,j,k) holds block row h = i + k*q of A and C (Alg. 3, set-up loop).     */
+
+int64_t orc_block_row(int q, int i, int k) { return (int64_t)i + (int64_t)k * q; }
+
+/* Returns 0 when the grid and sizes are admissible: 1 <= d <= q
+ * (Section 3.1), coordinates inside the grid, and the sizes divisible so that
+ * every block has the shape [a/(qd), b/q], [b/q, c/q], [a/(qd), c/q].       */
+int orc_check_grid(int q, int d, int i, int j, int k, int64_t a, int64_t b, int64_t c)
+{
+    if (q < 1 || d < 1 || d > q) return 1;
+    if (i < 0 || i >= q || j < 0 || j >= q || k < 0 || k >= d) return 1;
+    if (a < 1 || b < 1 || c < 1) return 2;
+    if (a % ((int64_t)q * d) != 0 || b % q != 0 || c % q != 0) return 2;
+    return 0;
+}
+
+/* ---- per-processor formulas on panels ------------------------------------
+ * A "panel" is one block that the paper delivers by a row or column
+ * broadcast at step t.  Panels are row-major with a leading dimension in
+ * elements.  `rows`/`n_rows` select a subset of OUTPUT rows (NULL = all);
+ * out is packed [n_rows_or_all, width].                                     */
+
+/* Forward, Alg. 3 inner loop plus the bias/activation that follow it:
+ *   Z[r,s] = sum_{t<q} sum_{u<kb} A_t[r,u] * B_t[u,s]
+ *   Y[r,s] = act(Z[r,s] + bias[s])
+ * a_panels[t]: [m,kb] (the block A_{i,t,k}); b_panels[t]: [kb,n] (B_{t,j});
+ * bias: [n] slice j of the bias or NULL.  z_out (optional) receives Z+bias. */
+void orc_fwd_panels(int q, int64_t m, int64_t kb, int64_t n,
+                    const double* const* a_panels, int64_t lda,
+                    const double* const* b_panels, int64_t ldb,
+                    const double* bias, int act,
+                    const int64_t* rows, int64_t n_rows,
+                    double* y_out, double* z_out)
+{
+    const int64_t R = rows ? n_rows : m;
+#pragma omp parallel for schedule(static)
+    for (int64_t rr = 0; rr < R; ++rr) {
+        const int64_t r = rows ? rows[rr] : rr;
+        double* acc = y_out + rr * n;
+        for (int64_t s = 0; s < n; ++s) acc[s] = 0.0;
+        for (int t = 0; t < q; ++t) {
+            const double* At = a_panels[t];
+            const double* Bt = b_panels[t];
+            for (int64_t u = 0; u < kb; ++u) {
+                const double av = At[r * lda + u];
+                const double* brow = Bt + u * ldb;
+                for (int64_t s = 0; s < n; ++s) acc[s] += av * brow[s];
+            }
+        }
+        for (int64_t s = 0; s < n; ++s) {
+            const double z = acc[s] + (bias ? bias[s] : 0.0);
+            if (z_out) z_out[rr * n + s] = z;
+            acc[s] = orc_act(z, act);
+        }
+    }
+}
+
+/* Input gradient (A' = C' B^T of the SUMMA gradient equation, evaluated on
+ * the owner of the block):
+ *   dX[r,u] = sum_{t<q} sum_{s<n} dY_t[r,s] * W_t[u,s]
+ * dy_panels[t]: [m,n] (dY_{i,t,k}); w_panels[t]: [kb,n] (W_{j,t}).          */
+void orc_bwd_dx_panels(int q, int64_t m, int64_t kb, int64_t n,
+                       const double* const* dy_panels, int64_t lddy,
+                       const double* const* w_panels, int64_t ldw,
+                       const int64_t* rows, int64_t n_rows, double* dx_out)
+{
+    const int64_t R = rows ? n_rows : m;
+#pragma omp parallel for schedule(static)
+    for (int64_t rr = 0; rr < R; ++rr) {
+        const int64_t r = rows ? rows[rr] : rr;
+        for (int64_t u = 0; u < kb; ++u) {
+            double acc = 0.0;
+            for (int t = 0; t < q; ++t) {
+                const double* dyrow = dy_panels[t] + r * lddy;
+                const double* wrow = w_panels[t] + u * ldw;
+                for (int64_t s = 0; s < n; ++s) acc += dyrow[s] * wrow[s];
+            }
+            dx_out[rr * kb + u] = acc;
+        }
+    }
+}
+
+/* Weight gradient of one depth layer (B' = A^T C'):
+ *   dW[u,s] = sum_{t<q} sum_{r<m} X_t[r,u] * dY_t[r,s]
+ * x_panels[t]: [m,kb] (X_{t,i,k}); dy_panels[t]: [m,n] (dY_{t,j,k}).  When
+ * `accumulate` is non-zero the result is added to dw_out (the sum over the d
+ * depth layers that Section 3.1 obtains with an all-reduce).                */
+void orc_bwd_dw_panels(int q, int64_t m, int64_t kb, int64_t n,
+                       const double* const* x_panels, int64_t ldx,
+                       const double* const* dy_panels, int64_t lddy,
+                       const int64_t* rows, int64_t n_rows,
+                       int accumulate, double* dw_out)
+{
+    const int64_t R = rows ? n_rows : kb;
+#pragma omp parallel for schedule(static)
+    for (int64_t uu = 0; uu < R; ++uu) {
+        const int64_t u = rows ? rows[uu] : uu;
+        double* acc = (double*)malloc((size_t)n * sizeof(double));
+        for (int64_t s = 0; s < n; ++s) acc[s] = 0.0;
+        for (int t = 0; t < q; ++t) {
+            const double* Xt = x_panels[t];
+            const double* dYt = dy_panels[t];
+            for (int64_t r = 0; r < m; ++r) {
+                const double xv = Xt[r * ldx + u];
+                const double* dyrow = dYt + r * lddy;
+                for (int64_t s = 0; s < n; ++s) acc[s] += xv * dyrow[s];
+            }
+        }
+        double* orow = dw_out + uu * n;
+        for (int64_t s = 0; s < n; ++s) orow[s] = accumulate ? orow[s] + acc[s] : acc[s];
+        free(acc);
+    }
+}
+
+/* ---- per-processor formulas on the unpartitioned matrices ----------------
+ * These cut the blocks out of the global matrices exactly as Alg. 3 lays
+ * them out and hand them to the panel formulas above.                       */
+
+/* Y_{i,j,k} [a/(qd), c/q] from A[a,b], B[b,c], bias[c] (or NULL). */
+int orc_tess_fwd(int q, int d, int i, int j, int k, int64_t a, int64_t b, int64_t c,
+                 const double* A, const double* B, const double* bias, int act,
+                 double* y_block, double* z_block)
+{
+    int rc = orc_check_grid(q, d, i, j, k, a, b, c);
+    if (rc) return rc;
+    const int64_t m = a / ((int64_t)q * d), kb = b / q, n = c / q;
+    const int64_t h = orc_block_row(q, i, k);
+    const double** ap = (const double**)malloc(sizeof(double*) * q);
+    const double** bp = (const double**)malloc(sizeof(double*) * q);
+    for (int t = 0; t < q; ++t) {
+        ap[t] = A + (h * m) * b + (int64_t)t * kb;       /* A_{i,t,k}: block (h, t) */
+        bp[t] = B + ((int64_t)t * kb) * c + (int64_t)j * n; /* B_{t,j}              */
+    }
+    orc_fwd_panels(q, m, kb, n, ap, b, bp, c, bias ? bias + (int64_t)j * n : NULL, act,
+                   NULL, 0, y_block, z_block);
+    free(ap);
+    free(bp);
+    return 0;
+}
+
+/* dX_{i,j,k} [a/(qd), b/q] from dY[a,c], W[b,c]. */
+int orc_tess_bwd_dx(int q, int d, int i, int j, int k, int64_t a, int64_t b, int64_t c,
+                    const double* dY, const double* W, double* dx_block)
+{
+    int rc = orc_check_grid(q, d, i, j, k, a, b, c);
+    if (rc) return rc;
+    const int64_t m = a / ((int64_t)q * d), kb = b / q, n = c / q;
+    const int64_t h = orc_block_row(q, i, k);
+    const double** dyp = (const double**)malloc(sizeof(double*) * q);
+    const double** wp = (const double**)malloc(sizeof(double*) * q);
+    for (int t = 0; t < q; ++t) {
+        dyp[t] = dY + (h * m) * c + (int64_t)t * n;            /* dY_{i,t,k}        */
+        wp[t] = W + ((int64_t)j * kb) * c + (int64_t)t * n;    /* W_{j,t}           */
+    }
+    orc_bwd_dx_panels(q, m, kb, n, dyp, c, wp, c, NULL, 0, dx_block);
+    free(dyp);
+    free(wp);
+    return 0;
+}
+
+/* Depth-k partial dW^{(k)}_{i,j} [b/q, c/q] from X[a,b], dY[a,c]. */
+int orc_tess_bwd_dw(int q, int d, int i, int j, int k, int64_t a, int64_t b, int64_t c,
+                    const double* X, const double* dY, int accumulate, double* dw_block)
+{
+    int rc = orc_check_grid(q, d, i, j, k, a, b, c);
+    if (rc) return rc;
+    const int64_t m = a / ((int64_t)q * d), kb = b / q, n = c / q;
+    const double** xp = (const double**)malloc(sizeof(double*) * q);
+    const double** dyp = (const double**)malloc(sizeof(double*) * q);
+    for (int t = 0; t < q; ++t) {
+        const int64_t h = orc_block_row(q, t, k);
+        xp[t] = X + (h * m) * b + (int64_t)i * kb;    /* X_{t,i,k}: block (t+kq, i)  */
+        dyp[t] = dY + (h * m) * c + (int64_t)j * n;   /* dY_{t,j,k}                  */
+    }
+    orc_bwd_dw_panels(q, m, kb, n, xp, b, dyp, c, NULL, 0, accumulate, dw_block);
+    free(xp);
+    free(dyp);
+    return 0;
+}
+
+/* ||G - O||_F / ||O||_F ; returns ||G||_F when O is all zero. */
+double orc_rel_frobenius(const double* G, const double* O, int64_t count)
+{
+    double num = 0.0, den = 0.0;
+    for (int64_t e = 0; e < count; ++e) {
+        const double df = G[e] - O[e];
+        num += df * df;
+        den += O[e] * O[e];
+    }
+    if (den == 0.0) return sqrt(num);
+    return sqrt(num / den);
+}
