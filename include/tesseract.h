@@ -1,0 +1,142 @@
+/*
+ * tesseract.h -- C ABI of the MI355X (gfx950) library for the per-processor
+ * compute of a linear layer partitioned over a Tesseract [q, q, d] grid.
+ *
+ * Problem statement (Section 3.1 and Alg. 3 of the Tesseract paper): the
+ * p = d*q*q processors form a [q, q, d] grid, 1 <= d <= q.  A[a,b] is cut
+ * into q*d block rows and q block columns, B[b,c] into q x q blocks that every
+ * depth layer holds, C[a,c] like A.  Processor (i,j,k) owns block row
+ * h = i + k*q.  With m = a/(q*d), kb = b/q, n = c/q the blocks are [m,kb],
+ * [kb,n] and [m,n].  At step t = 0..q-1 the processor receives A_{i,t,k} by a
+ * broadcast along its grid row and B_{t,j} by a broadcast along its grid
+ * column and accumulates their product.  This library does the accumulation
+ * of all q steps in one kernel launch: the panels that the broadcasts would
+ * deliver are passed as q device pointers per operand.
+ *
+ * Conventions common to every entry point
+ *  - `*_panels` are HOST arrays of q DEVICE pointers.  The pointers are copied
+ *    into the kernel arguments at the call; the array may be freed afterwards.
+ *  - All matrices are row-major.  Leading dimensions (ld*) are in ELEMENTS and
+ *    are shared by the q panels of one operand, so a panel may be a packed
+ *    receive buffer (ld = row length) or a view into a larger matrix.
+ *  - Ownership: the caller owns every buffer, including the workspace.  The
+ *    library allocates nothing, keeps no state between calls and never
+ *    synchronises; kernels are enqueued on `hip_stream` (a hipStream_t cast to
+ *    void*, NULL = the default stream) of the current device.
+ *  - Errors: a status code is returned, nothing is thrown or aborted.  All
+ *    argument checks happen before the first HIP call, so they work on a
+ *    host without a GPU; on a non-OK status no output has been touched.
+ *  - Inputs must not alias outputs.  q <= TESS_MAX_Q.
+ *  - in_dtype TESS_BF16 computes bf16 x bf16 products on the matrix cores with
+ *    fp32 accumulation over all q steps; TESS_F32 uses fp32 fused multiply-add.
+ *    Down-casts to bf16 round to nearest, ties to even.
+ *  - Results are deterministic run to run (no floating-point atomics).
+ */
+#ifndef TESSERACT_H_
+#define TESSERACT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TESS_MAX_Q 16
+
+typedef enum {
+    TESS_OK = 0,
+    TESS_ERR_NULL = 1,        /* a required pointer (descriptor, panel, output) is NULL      */
+    TESS_ERR_GRID = 2,        /* q<1, d<1, d>q, q>TESS_MAX_Q or a coordinate outside the grid */
+    TESS_ERR_SHAPE = 3,       /* a%(q*d), b%q or c%q non-zero, a size < 1, or ld < row length */
+    TESS_ERR_ALIGN = 4,       /* reserved: alignment the selected kernel cannot serve         */
+    TESS_ERR_UNSUPPORTED = 5, /* dtype / activation / flag combination not implemented        */
+    TESS_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than tess_linear_workspace_bytes   */
+    TESS_ERR_HIP = 7          /* a HIP runtime call (kernel launch) failed                    */
+} tess_status;
+
+typedef enum { TESS_F32 = 0, TESS_BF16 = 1 } tess_dtype;
+
+/* Activation of the fused epilogue.  The paper's MLP has "an activation" between
+ * its two linear layers without naming it; GELU in its exact (erf) and tanh
+ * forms are offered. */
+typedef enum { TESS_ACT_NONE = 0, TESS_ACT_GELU_ERF = 1, TESS_ACT_GELU_TANH = 2 } tess_act;
+
+typedef enum { TESS_OP_FWD = 0, TESS_OP_BWD_DX = 1, TESS_OP_BWD_DW = 2 } tess_op;
+
+/* The problem as the paper states it: the grid, this processor's coordinates and
+ * the GLOBAL matrix sizes (Alg. 3 inputs). */
+typedef struct {
+    int32_t q, d;      /* grid [q, q, d], 1 <= d <= q                      */
+    int32_t i, j, k;   /* this processor: 0 <= i,j < q, 0 <= k < d         */
+    int64_t a, b, c;   /* A[a,b] (activations), B[b,c] (weights), C[a,c]   */
+    int32_t in_dtype;  /* tess_dtype of every input block (and of bias)    */
+    int32_t out_dtype; /* tess_dtype of c_out / preact_out / dx_out / dw_out
+                          (dw_out is fp32 regardless when accumulate != 0) */
+} tess_desc;
+
+/* Forward (Alg. 3 inner loop, then the bias add of Section 3.2.2 and the MLP
+ * activation):   C_{i,j,k} = act( sum_{t<q} A_{i,t,k} * B_{t,j} + bias_j ).
+ *   a_panels[t] : device, [m, kb], leading dimension lda   (block A_{i,t,k})
+ *   b_panels[t] : device, [kb, n], leading dimension ldb   (block B_{t,j})
+ *   bias        : device, [n] in in_dtype (slice j of the bias), or NULL
+ *   c_out       : device, [m, n], ldc, out_dtype
+ *   preact_out  : device, [m, n], ldc, out_dtype, or NULL: receives the sum plus
+ *                 bias before the activation (what a GELU backward needs)
+ *   workspace   : device scratch of >= tess_linear_workspace_bytes(desc, TESS_OP_FWD)
+ *                 bytes, 256-byte aligned; may be NULL when that size is 0.        */
+tess_status tess_linear_fwd(const tess_desc* desc,
+                            const void* const* a_panels, int64_t lda,
+                            const void* const* b_panels, int64_t ldb,
+                            const void* bias, int act,
+                            void* c_out, int64_t ldc, void* preact_out,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Input gradient (A' = C' B^T of the SUMMA gradient equation, Section 2.2; the
+ * C = A B^T procedure of Section 3.1), computed on the owner of the block:
+ *   dX_{i,j,k} = sum_{t<q} dY_{i,t,k} * (W_{j,t})^T.
+ *   dy_panels[t] : device, [m, n],  lddy   (block dY_{i,t,k})
+ *   w_panels[t]  : device, [kb, n], ldw    (block row j, block column t of W)
+ *   dx_out       : device, [m, kb], lddx, out_dtype                               */
+tess_status tess_linear_bwd_dx(const tess_desc* desc,
+                               const void* const* dy_panels, int64_t lddy,
+                               const void* const* w_panels, int64_t ldw,
+                               void* dx_out, int64_t lddx,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Weight gradient of depth layer k (B' = A^T C', Section 2.2; the C = A^T B
+ * procedure of Section 3.1):
+ *   dW^(k)_{i,j} = sum_{t<q} (X_{t,i,k})^T * dY_{t,j,k}.
+ *   x_panels[t]  : device, [m, kb], ldx    (block row t + k*q, block column i of X)
+ *   dy_panels[t] : device, [m, n],  lddy   (block row t + k*q, block column j of dY)
+ *   dw_out       : device, [kb, n], lddw
+ *   accumulate   : 0 -> dw_out (out_dtype) is overwritten.
+ *                  1 -> dw_out is fp32 and the result is ADDED to it: d calls with
+ *                  k = 0..d-1 into one buffer form the sum over the depth layers
+ *                  that Section 3.1 obtains with an all-reduce.                   */
+tess_status tess_linear_bwd_dw(const tess_desc* desc,
+                               const void* const* x_panels, int64_t ldx,
+                               const void* const* dy_panels, int64_t lddy,
+                               void* dw_out, int64_t lddw, int accumulate,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device scratch that the call `op` (a tess_op) needs for this
+ * descriptor on the current device (0 when none).  Pure host arithmetic. */
+size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
+
+/* Validates a descriptor alone (grid rules and divisibility). */
+tess_status tess_desc_check(const tess_desc* desc);
+
+/* Block shape of this descriptor: m = a/(q*d), kb = b/q, n = c/q. */
+tess_status tess_block_shape(const tess_desc* desc, int64_t* m, int64_t* kb, int64_t* n);
+
+/* Static, NUL-terminated name of a status code. */
+const char* tess_status_string(int status);
+
+/* Library version, "major.minor". */
+const char* tess_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TESSERACT_H_ */

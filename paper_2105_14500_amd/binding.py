@@ -1,0 +1,194 @@
+"""ctypes binding of the C ABI in include/tesseract.h.
+
+Argument marshalling only: tensors are turned into device pointers, leading
+dimensions and a stream handle; every step of the computation runs in the HIP
+library.  There is no CPU fallback: a missing library raises at first use.
+PyTorch is used for device memory and streams.
+"""
+import ctypes
+import os
+
+import torch
+
+F32, BF16 = 0, 1
+ACT_NONE, ACT_GELU_ERF, ACT_GELU_TANH = 0, 1, 2
+OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
+MAX_Q = 16
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
+
+EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
+           "tess_linear_workspace_bytes", "tess_desc_check", "tess_block_shape",
+           "tess_status_string", "tess_version"]
+
+
+class TessDesc(ctypes.Structure):
+    """Mirror of `tess_desc`: grid [q,q,d], coordinates (i,j,k), global sizes a,b,c."""
+    _fields_ = [("q", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("i", ctypes.c_int32), ("j", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("a", ctypes.c_int64), ("b", ctypes.c_int64), ("c", ctypes.c_int64),
+                ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32)]
+
+
+class TessError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library (built in-tree by paper_2105_14500_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2105_14500_amd.build` "
+                               "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, cint, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+        dp = ctypes.POINTER(TessDesc)
+        pp = ctypes.POINTER(ctypes.c_void_p)
+        L.tess_linear_fwd.restype = cint
+        L.tess_linear_fwd.argtypes = [dp, pp, i64, pp, i64, vp, cint, vp, i64, vp, vp, sz, vp]
+        L.tess_linear_bwd_dx.restype = cint
+        L.tess_linear_bwd_dx.argtypes = [dp, pp, i64, pp, i64, vp, i64, vp, sz, vp]
+        L.tess_linear_bwd_dw.restype = cint
+        L.tess_linear_bwd_dw.argtypes = [dp, pp, i64, pp, i64, vp, i64, cint, vp, sz, vp]
+        L.tess_linear_workspace_bytes.restype = sz
+        L.tess_linear_workspace_bytes.argtypes = [dp, cint]
+        L.tess_desc_check.restype = cint
+        L.tess_desc_check.argtypes = [dp]
+        L.tess_block_shape.restype = cint
+        L.tess_block_shape.argtypes = [dp, ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                       ctypes.POINTER(i64)]
+        L.tess_status_string.restype = ctypes.c_char_p
+        L.tess_status_string.argtypes = [cint]
+        L.tess_version.restype = ctypes.c_char_p
+        L.tess_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().tess_status_string(int(status)).decode()
+
+
+def version():
+    return lib().tess_version().decode()
+
+
+def dtype_code(dt):
+    if dt == torch.float32:
+        return F32
+    if dt == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {dt}")
+
+
+def make_desc(q, d, i, j, k, a, b, c, in_dtype=BF16, out_dtype=BF16):
+    return TessDesc(q, d, i, j, k, a, b, c, in_dtype, out_dtype)
+
+
+def desc_check(desc):
+    return lib().tess_desc_check(ctypes.byref(desc))
+
+
+def block_shape(desc):
+    m, kb, n = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    st = lib().tess_block_shape(ctypes.byref(desc), ctypes.byref(m), ctypes.byref(kb),
+                                ctypes.byref(n))
+    if st:
+        raise TessError(st, "tess_block_shape")
+    return m.value, kb.value, n.value
+
+
+def workspace_bytes(desc, op):
+    return lib().tess_linear_workspace_bytes(ctypes.byref(desc), op)
+
+
+def _panel_array(panels, rows, cols, what):
+    """q 2-D device tensors with unit column stride and one common row stride ->
+    (host array of device pointers, leading dimension in elements)."""
+    ld = None
+    ptrs = (ctypes.c_void_p * len(panels))()
+    for t, p in enumerate(panels):
+        if p.dim() != 2 or tuple(p.shape) != (rows, cols):
+            raise ValueError(f"{what}[{t}] has shape {tuple(p.shape)}, expected {(rows, cols)}")
+        if not p.is_cuda:
+            raise ValueError(f"{what}[{t}] is not a device tensor")
+        if p.stride(1) != 1 and cols > 1:
+            raise ValueError(f"{what}[{t}] rows are not contiguous")
+        l = p.stride(0) if rows > 1 else max(p.stride(0), cols)
+        if ld is None:
+            ld = l
+        elif l != ld:
+            raise ValueError(f"{what}: panels differ in leading dimension")
+        ptrs[t] = p.data_ptr()
+    return ptrs, ld
+
+
+def _out(t, rows, cols, what):
+    if t.dim() != 2 or tuple(t.shape) != (rows, cols) or not t.is_cuda or (cols > 1 and t.stride(1) != 1):
+        raise ValueError(f"{what}: need a device tensor of shape {(rows, cols)} with contiguous rows")
+    return ctypes.c_void_p(t.data_ptr()), (t.stride(0) if rows > 1 else max(t.stride(0), cols))
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def linear_fwd(desc, a_panels, b_panels, bias, act, c_out, preact_out=None, workspace=None,
+               stream=None):
+    """tess_linear_fwd: c_out = act(sum_t a_panels[t] @ b_panels[t] + bias)."""
+    m, kb, n = block_shape(desc)
+    ap, lda = _panel_array(a_panels, m, kb, "a_panels")
+    bp, ldb = _panel_array(b_panels, kb, n, "b_panels")
+    cp, ldc = _out(c_out, m, n, "c_out")
+    pre = None
+    if preact_out is not None:
+        pre, ldp = _out(preact_out, m, n, "preact_out")
+        if ldp != ldc:
+            raise ValueError("preact_out must share c_out's leading dimension")
+    bptr = ctypes.c_void_p(bias.data_ptr()) if bias is not None else None
+    wsp, wsb = _ws(workspace)
+    st = lib().tess_linear_fwd(ctypes.byref(desc), ap, lda, bp, ldb, bptr, act, cp, ldc, pre,
+                               wsp, wsb, _stream(stream))
+    if st:
+        raise TessError(st, "tess_linear_fwd")
+
+
+def linear_bwd_dx(desc, dy_panels, w_panels, dx_out, workspace=None, stream=None):
+    """tess_linear_bwd_dx: dx_out = sum_t dy_panels[t] @ w_panels[t]^T."""
+    m, kb, n = block_shape(desc)
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels")
+    wp, ldw = _panel_array(w_panels, kb, n, "w_panels")
+    op, ldo = _out(dx_out, m, kb, "dx_out")
+    wsp, wsb = _ws(workspace)
+    st = lib().tess_linear_bwd_dx(ctypes.byref(desc), dyp, lddy, wp, ldw, op, ldo, wsp, wsb,
+                                  _stream(stream))
+    if st:
+        raise TessError(st, "tess_linear_bwd_dx")
+
+
+def linear_bwd_dw(desc, x_panels, dy_panels, dw_out, accumulate=False, workspace=None,
+                  stream=None):
+    """tess_linear_bwd_dw: dw_out (+)= sum_t x_panels[t]^T @ dy_panels[t]."""
+    m, kb, n = block_shape(desc)
+    xp, ldx = _panel_array(x_panels, m, kb, "x_panels")
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels")
+    op, ldo = _out(dw_out, kb, n, "dw_out")
+    wsp, wsb = _ws(workspace)
+    st = lib().tess_linear_bwd_dw(ctypes.byref(desc), xp, ldx, dyp, lddy, op, ldo,
+                                  1 if accumulate else 0, wsp, wsb, _stream(stream))
+    if st:
+        raise TessError(st, "tess_linear_bwd_dw")

@@ -1,0 +1,226 @@
+// Host side of the C ABI declared in include/tesseract.h: argument validation,
+// mapping of the three Tesseract products onto one batched-panel GEMM launch,
+// kernel/tile/split selection.  No HIP call happens before validation has passed.
+#include "tess_internal.h"
+
+namespace tess {
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape-only part of the plan (what tess_linear_workspace_bytes can know).
+static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
+{
+    Plan p{};
+    p.path = Path::Generic;
+    p.bm = p.bn = 0;
+    p.splits = 1;
+    p.direct = 0;
+    p.ws_bytes = 0;
+    if (!in_bf16) return p;
+    p.path = Path::Mfma;
+    // 256 x 256 tiles when that still gives the 256 compute units enough work,
+    // otherwise 128 x 128
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t kt_total = (int64_t)q * ((Kp + BK_HOST - 1) / BK_HOST);
+    if (M >= 256 && N >= 256 && t256 * (kt_total >= 8 ? 8 : 1) >= 192) {
+        p.bm = p.bn = 256;
+    } else {
+        p.bm = p.bn = 128;
+    }
+    const int64_t tiles = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
+    // split the K loop when one wave of tiles leaves most compute units idle
+    int splits = 1;
+    if (tiles < 160) {
+        splits = (int)((256 + tiles - 1) / tiles);
+        const int64_t max_by_k = kt_total / 8 > 0 ? kt_total / 8 : 1;   // >= 8 stages per split
+        if (splits > max_by_k) splits = (int)max_by_k;
+        if (splits > 32) splits = 32;
+        if (splits < 1) splits = 1;
+    }
+    p.splits = splits;
+    p.direct = (Kp % BK_HOST == 0) ? 1 : 0;
+    if (splits > 1) p.ws_bytes = (size_t)splits * tiles * p.bm * p.bn * sizeof(float);
+    return p;
+}
+
+Plan make_plan(const GemmArgs& g)
+{
+    Plan p = shape_plan(g.M, g.N, g.Kp, g.q, !g.in_f32);
+    if (p.path == Path::Mfma) {
+        // requirements of the 16-byte granule loaders
+        bool ok = (g.lda % 8 == 0) && (g.ldb % 8 == 0);
+        if (g.a_kc) ok = ok && (g.Kp % 8 == 0); else ok = ok && (g.M % 8 == 0) && g.M >= 8;
+        if (g.b_kc) ok = ok && (g.Kp % 8 == 0); else ok = ok && (g.N % 8 == 0) && g.N >= 8;
+        for (int t = 0; t < g.q && ok; ++t) ok = aligned16(g.a[t]) && aligned16(g.b[t]);
+        // 32-bit byte offsets inside a panel
+        const int64_t a_rows = g.a_kc ? g.M : g.Kp, b_rows = g.b_kc ? g.N : g.Kp;
+        ok = ok && (a_rows * g.lda * 2 < (int64_t)1 << 32) && (b_rows * g.ldb * 2 < (int64_t)1 << 32);
+        if (!ok) {
+            p.path = Path::Generic;
+            p.splits = 1;
+            p.ws_bytes = 0;
+        }
+    }
+    return p;
+}
+
+static tess_status check_desc(const tess_desc* d)
+{
+    if (!d) return TESS_ERR_NULL;
+    if (d->q < 1 || d->d < 1 || d->d > d->q || d->q > TESS_MAX_Q) return TESS_ERR_GRID;
+    if (d->i < 0 || d->i >= d->q || d->j < 0 || d->j >= d->q || d->k < 0 || d->k >= d->d)
+        return TESS_ERR_GRID;
+    if (d->a < 1 || d->b < 1 || d->c < 1) return TESS_ERR_SHAPE;
+    if (d->a % ((int64_t)d->q * d->d) != 0 || d->b % d->q != 0 || d->c % d->q != 0)
+        return TESS_ERR_SHAPE;
+    if (d->in_dtype != TESS_F32 && d->in_dtype != TESS_BF16) return TESS_ERR_UNSUPPORTED;
+    if (d->out_dtype != TESS_F32 && d->out_dtype != TESS_BF16) return TESS_ERR_UNSUPPORTED;
+    const int64_t lim = (int64_t)1 << 30;
+    if (d->a / ((int64_t)d->q * d->d) >= lim || d->b / d->q >= lim || d->c / d->q >= lim)
+        return TESS_ERR_UNSUPPORTED;
+    return TESS_OK;
+}
+
+static tess_status check_panels(const void* const* p, int q)
+{
+    if (!p) return TESS_ERR_NULL;
+    for (int t = 0; t < q; ++t)
+        if (!p[t]) return TESS_ERR_NULL;
+    return TESS_OK;
+}
+
+static tess_status run(GemmArgs& g, void* workspace, size_t workspace_bytes, void* stream)
+{
+    const Plan p = make_plan(g);
+    if (p.ws_bytes > 0) {
+        if (!workspace || workspace_bytes < p.ws_bytes) return TESS_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return TESS_ERR_WORKSPACE;
+        g.ws = static_cast<float*>(workspace);
+    }
+    g.splits = p.splits;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = (p.path == Path::Mfma) ? launch_mfma(g, p, s) : launch_generic(g, s);
+    return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
+}
+
+}  // namespace tess
+
+using namespace tess;
+
+extern "C" {
+
+tess_status tess_desc_check(const tess_desc* desc) { return check_desc(desc); }
+
+tess_status tess_block_shape(const tess_desc* desc, int64_t* m, int64_t* kb, int64_t* n)
+{
+    tess_status st = check_desc(desc);
+    if (st != TESS_OK) return st;
+    if (!m || !kb || !n) return TESS_ERR_NULL;
+    *m = desc->a / ((int64_t)desc->q * desc->d);
+    *kb = desc->b / desc->q;
+    *n = desc->c / desc->q;
+    return TESS_OK;
+}
+
+size_t tess_linear_workspace_bytes(const tess_desc* desc, int op)
+{
+    if (check_desc(desc) != TESS_OK) return 0;
+    const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
+                  n = desc->c / desc->q;
+    const bool bf = desc->in_dtype == TESS_BF16;
+    switch (op) {
+        case TESS_OP_FWD: return shape_plan(m, n, kb, desc->q, bf).ws_bytes;
+        case TESS_OP_BWD_DX: return shape_plan(m, kb, n, desc->q, bf).ws_bytes;
+        case TESS_OP_BWD_DW: return shape_plan(kb, n, m, desc->q, bf).ws_bytes;
+        default: return 0;
+    }
+}
+
+tess_status tess_linear_fwd(const tess_desc* desc, const void* const* a_panels, int64_t lda,
+                            const void* const* b_panels, int64_t ldb, const void* bias, int act,
+                            void* c_out, int64_t ldc, void* preact_out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream)
+{
+    tess_status st = check_desc(desc);
+    if (st != TESS_OK) return st;
+    if ((st = check_panels(a_panels, desc->q)) != TESS_OK) return st;
+    if ((st = check_panels(b_panels, desc->q)) != TESS_OK) return st;
+    if (!c_out) return TESS_ERR_NULL;
+    if (act != TESS_ACT_NONE && act != TESS_ACT_GELU_ERF && act != TESS_ACT_GELU_TANH)
+        return TESS_ERR_UNSUPPORTED;
+    const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
+                  n = desc->c / desc->q;
+    if (lda < kb || ldb < n || ldc < n) return TESS_ERR_SHAPE;
+    GemmArgs g{};
+    for (int t = 0; t < desc->q; ++t) { g.a[t] = a_panels[t]; g.b[t] = b_panels[t]; }
+    g.q = desc->q; g.M = (int32_t)m; g.N = (int32_t)n; g.Kp = (int32_t)kb;
+    g.lda = lda; g.ldb = ldb; g.out = c_out; g.ldo = ldc; g.preact = preact_out; g.bias = bias;
+    g.act = act; g.out_f32 = desc->out_dtype == TESS_F32; g.accumulate = 0;
+    g.a_kc = 1; g.b_kc = 0; g.in_f32 = desc->in_dtype == TESS_F32;
+    return run(g, workspace, workspace_bytes, hip_stream);
+}
+
+tess_status tess_linear_bwd_dx(const tess_desc* desc, const void* const* dy_panels, int64_t lddy,
+                               const void* const* w_panels, int64_t ldw, void* dx_out,
+                               int64_t lddx, void* workspace, size_t workspace_bytes,
+                               void* hip_stream)
+{
+    tess_status st = check_desc(desc);
+    if (st != TESS_OK) return st;
+    if ((st = check_panels(dy_panels, desc->q)) != TESS_OK) return st;
+    if ((st = check_panels(w_panels, desc->q)) != TESS_OK) return st;
+    if (!dx_out) return TESS_ERR_NULL;
+    const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
+                  n = desc->c / desc->q;
+    if (lddy < n || ldw < n || lddx < kb) return TESS_ERR_SHAPE;
+    GemmArgs g{};
+    for (int t = 0; t < desc->q; ++t) { g.a[t] = dy_panels[t]; g.b[t] = w_panels[t]; }
+    g.q = desc->q; g.M = (int32_t)m; g.N = (int32_t)kb; g.Kp = (int32_t)n;
+    g.lda = lddy; g.ldb = ldw; g.out = dx_out; g.ldo = lddx; g.preact = nullptr; g.bias = nullptr;
+    g.act = TESS_ACT_NONE; g.out_f32 = desc->out_dtype == TESS_F32; g.accumulate = 0;
+    g.a_kc = 1; g.b_kc = 1; g.in_f32 = desc->in_dtype == TESS_F32;
+    return run(g, workspace, workspace_bytes, hip_stream);
+}
+
+tess_status tess_linear_bwd_dw(const tess_desc* desc, const void* const* x_panels, int64_t ldx,
+                               const void* const* dy_panels, int64_t lddy, void* dw_out,
+                               int64_t lddw, int accumulate, void* workspace,
+                               size_t workspace_bytes, void* hip_stream)
+{
+    tess_status st = check_desc(desc);
+    if (st != TESS_OK) return st;
+    if ((st = check_panels(x_panels, desc->q)) != TESS_OK) return st;
+    if ((st = check_panels(dy_panels, desc->q)) != TESS_OK) return st;
+    if (!dw_out) return TESS_ERR_NULL;
+    if (accumulate != 0 && accumulate != 1) return TESS_ERR_UNSUPPORTED;
+    const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
+                  n = desc->c / desc->q;
+    if (ldx < kb || lddy < n || lddw < n) return TESS_ERR_SHAPE;
+    GemmArgs g{};
+    for (int t = 0; t < desc->q; ++t) { g.a[t] = x_panels[t]; g.b[t] = dy_panels[t]; }
+    g.q = desc->q; g.M = (int32_t)kb; g.N = (int32_t)n; g.Kp = (int32_t)m;
+    g.lda = ldx; g.ldb = lddy; g.out = dw_out; g.ldo = lddw; g.preact = nullptr; g.bias = nullptr;
+    g.act = TESS_ACT_NONE; g.out_f32 = accumulate ? 1 : (desc->out_dtype == TESS_F32);
+    g.accumulate = accumulate;
+    g.a_kc = 0; g.b_kc = 0; g.in_f32 = desc->in_dtype == TESS_F32;
+    return run(g, workspace, workspace_bytes, hip_stream);
+}
+
+const char* tess_status_string(int status)
+{
+    switch (status) {
+        case TESS_OK: return "TESS_OK";
+        case TESS_ERR_NULL: return "TESS_ERR_NULL";
+        case TESS_ERR_GRID: return "TESS_ERR_GRID";
+        case TESS_ERR_SHAPE: return "TESS_ERR_SHAPE";
+        case TESS_ERR_ALIGN: return "TESS_ERR_ALIGN";
+        case TESS_ERR_UNSUPPORTED: return "TESS_ERR_UNSUPPORTED";
+        case TESS_ERR_WORKSPACE: return "TESS_ERR_WORKSPACE";
+        case TESS_ERR_HIP: return "TESS_ERR_HIP";
+        default: return "TESS_ERR_?";
+    }
+}
+
+const char* tess_version(void) { return "0.1"; }
+
+}  // extern "C"

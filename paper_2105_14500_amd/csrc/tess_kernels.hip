@@ -1,0 +1,482 @@
+// HIP kernels (gfx950 / CDNA4) for the per-processor compute of a Tesseract
+// [q,q,d]-partitioned linear layer: the q-step block accumulation of Alg. 3 and
+// its two transposed variants (Section 3.1), with the bias/activation epilogue.
+//
+// Two kernel families:
+//   * tess_mfma_kernel   bf16 inputs, v_mfma_f32_32x32x16_bf16, fp32 accumulators
+//     that stay in registers over all q steps; operand tiles go through LDS.
+//   * tess_generic_kernel  any shape / alignment / fp32 inputs, fp32 FMA.
+#include "tess_internal.h"
+
+namespace tess {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+#define GLB_PTR(T) __attribute__((address_space(1))) T*
+
+constexpr int BK = 64;          // K extent of one LDS stage (bf16 elements)
+constexpr int NTHREADS = 256;   // 4 wavefronts, arranged 2 x 2 over the macro tile
+
+// ---------------------------------------------------------------------------
+// epilogue helpers
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float gelu_erf_f(float x)
+{
+    return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_tanh_f(float x)
+{
+    const float c = 0.79788456080286535588f;
+    return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
+}
+__device__ __forceinline__ float apply_act(float z, int act)
+{
+    if (act == TESS_ACT_GELU_ERF) return gelu_erf_f(z);
+    if (act == TESS_ACT_GELU_TANH) return gelu_tanh_f(z);
+    return z;
+}
+// fp32 -> bf16 bits, round to nearest even (NaN kept quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b)
+{
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+__device__ __forceinline__ float load_in(const void* p, int64_t idx, int in_f32)
+{
+    return in_f32 ? ((const float*)p)[idx] : bf16_bits_to_f32(((const uint16_t*)p)[idx]);
+}
+
+// value `acc` of output element (row, col): bias, optional pre-activation copy,
+// activation, accumulate, down-cast, store.
+__device__ __forceinline__ void store_out(const GemmArgs& g, int row, int col, float acc,
+                                          float bias_v)
+{
+    float z = acc + bias_v;
+    const int64_t o = (int64_t)row * g.ldo + col;
+    if (g.preact) {
+        if (g.out_f32) ((float*)g.preact)[o] = z;
+        else ((uint16_t*)g.preact)[o] = f32_to_bf16_bits(z);
+    }
+    float y = apply_act(z, g.act);
+    if (g.out_f32) {
+        float* op = (float*)g.out + o;
+        *op = g.accumulate ? (*op + y) : y;
+    } else {
+        ((uint16_t*)g.out)[o] = f32_to_bf16_bits(y);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// generic kernel: 64 x 64 output tile per 256 threads, 4 x 4 outputs per thread,
+// any shape, strides and alignment; inputs fp32 or bf16; fp32 FMA, contracted
+// index ascending within a panel and panels in ascending step order.
+// ---------------------------------------------------------------------------
+constexpr int GT = 64;   // tile edge
+constexpr int GK = 16;   // K step
+
+__global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
+{
+    __shared__ float As[GK][GT + 4];
+    __shared__ float Bs[GK][GT + 4];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int row0 = blockIdx.y * GT, col0 = blockIdx.x * GT;
+    // element (row, kk) of the A operand: a_kc ? [row*lda + kk] : [kk*lda + row]
+    const int64_t a_rs = g.a_kc ? g.lda : 1, a_ks = g.a_kc ? 1 : g.lda;
+    // element (kk, col) of the B operand: b_kc ? [col*ldb + kk] : [kk*ldb + col]
+    const int64_t b_cs = g.b_kc ? g.ldb : 1, b_ks = g.b_kc ? 1 : g.ldb;
+    float acc[4][4] = {};
+    for (int t = 0; t < g.q; ++t) {
+        const void* Ap = g.a[t];
+        const void* Bp = g.b[t];
+        for (int k0 = 0; k0 < g.Kp; k0 += GK) {
+            for (int e = tid; e < GK * GT; e += 256) {
+                int kk, rr;
+                if (g.a_kc) { kk = e % GK; rr = e / GK; } else { rr = e % GT; kk = e / GT; }
+                const int row = row0 + rr, kidx = k0 + kk;
+                As[kk][rr] = (row < g.M && kidx < g.Kp)
+                                 ? load_in(Ap, row * a_rs + kidx * a_ks, g.in_f32) : 0.0f;
+                int kb, cc;
+                if (g.b_kc) { kb = e % GK; cc = e / GK; } else { cc = e % GT; kb = e / GT; }
+                const int col = col0 + cc, kidb = k0 + kb;
+                Bs[kb][cc] = (col < g.N && kidb < g.Kp)
+                                 ? load_in(Bp, kidb * b_ks + col * b_cs, g.in_f32) : 0.0f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < GK; ++kk) {
+                float av[4], bv[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) { av[x] = As[kk][ty * 4 + x]; bv[x] = Bs[kk][tx * 4 + x]; }
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+#pragma unroll
+                    for (int y = 0; y < 4; ++y) acc[x][y] = fmaf(av[x], bv[y], acc[x][y]);
+            }
+            __syncthreads();
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int row = row0 + ty * 4 + x;
+        if (row >= g.M) continue;
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            const int col = col0 + tx * 4 + y;
+            if (col >= g.N) continue;
+            const float bv = g.bias ? load_in(g.bias, col, g.in_f32) : 0.0f;
+            store_out(g, row, col, acc[x][y], bv);
+        }
+    }
+}
+
+hipError_t launch_generic(const GemmArgs& g, hipStream_t s)
+{
+    dim3 grid((g.N + GT - 1) / GT, (g.M + GT - 1) / GT, 1);
+    hipLaunchKernelGGL(tess_generic_kernel, grid, dim3(256), 0, s, g);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// MFMA path
+// ---------------------------------------------------------------------------
+// LDS tile formats, in 16-byte granules (8 bf16):
+//  KC operand, R rows x 64 k:  granule (r, pc) at index r*8 + pc holds k-chunk
+//      c = pc ^ swz_kc(r) of row r.  A 32x32x16 fragment read (lane -> row l%32,
+//      chunk 2*kk + l/32, one 128-bit read) then touches every bank once per
+//      16 consecutive rows.
+//  MC operand, 64 k-rows x R elements: granule (kr, pg) at index kr*(R/8) + pg
+//      holds elements 8g..8g+7, g = pg ^ swz_mc(kr), of k-row kr.  Fragments are
+//      read with the transposing 64-bit LDS read, which hands lane s of a 16-lane
+//      group the 4 k-values of column s from 4 k-rows.
+// Tiles are always written linearly (granule index = it*256 + thread), so the
+// swizzle is applied on the global-memory side of the copy.
+__device__ __forceinline__ int swz_kc(int r) { return (r >> 1) & 7; }
+__device__ __forceinline__ int swz_mc(int kr) { return ((kr & 3) << 2) ^ (((kr >> 3) & 1) << 1); }
+
+template <int R, bool KC, bool DIRECT>
+struct TileLoader {
+    static constexpr int NG = R * 8;             // granules per stage
+    static constexpr int ITERS = NG / NTHREADS;
+    static constexpr int RG = R / 8;             // granules per k-row (MC)
+    uint32_t off[ITERS];    // byte offset of this thread's granule inside a panel at k0 = 0
+    uint32_t kpos[ITERS];   // k index (within the 64-wide stage) that the granule starts at
+    u32x4 stage[DIRECT ? 1 : ITERS];
+
+    // origin: first row (KC) / first element along R (MC) of this block's tile;
+    // extent: total rows / elements of the operand along R; ld in elements.
+    __device__ __forceinline__ void init(int tid, int origin, int extent, int64_t ld)
+    {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int G = it * NTHREADS + tid;
+            if (KC) {
+                const int r = G >> 3, pc = G & 7;
+                const int c = pc ^ swz_kc(r);
+                int row = origin + r;
+                row = row < extent ? row : extent - 1;
+                off[it] = (uint32_t)(((int64_t)row * ld + 8 * c) * 2);
+                kpos[it] = 8 * c;
+            } else {
+                const int kr = G / RG, pg = G % RG;
+                const int gidx = pg ^ swz_mc(kr);
+                int col = origin + 8 * gidx;
+                col = col + 8 <= extent ? col : extent - 8;
+                off[it] = (uint32_t)(((int64_t)kr * ld + col) * 2);
+                kpos[it] = kr;
+            }
+        }
+    }
+
+    // base: panel pointer advanced to the stage's first k (uniform); krem: number of
+    // valid k from there (only used by the staged variant, for the zero-filled tail).
+    __device__ __forceinline__ void issue(const char* base, char* lds_tile, int tid, int krem)
+    {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            if (DIRECT) {
+                const int wave_first = (it * NTHREADS + (tid & ~63)) * 16;
+                __builtin_amdgcn_global_load_lds((const GLB_PTR(void))(base + off[it]),
+                                                 (LDS_PTR(void))(lds_tile + wave_first), 16, 0, 0);
+            } else {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if ((int)kpos[it] < krem) v = *(const u32x4*)(base + off[it]);
+                stage[it] = v;
+            }
+        }
+    }
+    __device__ __forceinline__ void commit(char* lds_tile, int tid)
+    {
+        if (!DIRECT) {
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it)
+                *(u32x4*)(lds_tile + (it * NTHREADS + tid) * 16) = stage[it];
+        }
+    }
+};
+
+// Fragment reader: 32 (rows along R) x 16 (k) bf16 operand fragment for
+// v_mfma_f32_32x32x16_bf16: lane l gets row l%32, k = 8*(l/32) .. +7.
+template <int R, bool KC>
+struct FragReader {
+    uint32_t lane_off;      // per-lane byte offset, fragment 0
+    uint32_t kcol[4];       // KC: byte offset of the k-chunk for each of the 4 k16 steps
+    __device__ __forceinline__ void init(int lane, int wave_origin)
+    {
+        if (KC) {
+            const int r = wave_origin + (lane & 31);
+            lane_off = (uint32_t)r * 128u;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) kcol[kk] = (uint32_t)(((2 * kk + (lane >> 5)) ^ swz_kc(r)) * 16);
+        } else {
+            const int s = lane & 15, bl = lane >> 4;
+            const int kr = 8 * (bl >> 1) + (s >> 2);           // k-row inside a k16 step, h = 0
+            lane_off = (uint32_t)(kr * (R / 8) * 16 + (s & 1) * 8);
+            kcol[0] = (uint32_t)swz_mc(kr);
+            kcol[1] = (uint32_t)(wave_origin + 16 * (bl & 1) + 4 * (s & 3)) >> 3;  // granule of frag 0
+            kcol[2] = kcol[3] = 0;
+        }
+    }
+    // f: fragment index along R inside the wave tile, kk: k16 step of the stage
+    __device__ __forceinline__ bf16x8 read(const char* lds_tile, int f, int kk) const
+    {
+        if (KC) {
+            return *(const bf16x8*)(lds_tile + lane_off + f * (32 * 128) + kcol[kk]);
+        } else {
+            const uint32_t gsw = ((kcol[1] + 4u * f) ^ kcol[0]) * 16u;
+            const char* p = lds_tile + lane_off + gsw + kk * (16 * (R / 8) * 16);
+            bf16x4 lo = __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                                       (LDS_PTR(short4v))(p)));
+            bf16x4 hi = __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                                       (LDS_PTR(short4v))(p + 4 * (R / 8) * 16)));
+            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    }
+};
+
+// Accumulator layout of one 32x32 fragment: lane l, register r ->
+//   row = 8*(r/4) + 4*(l/32) + r%4,  col = l%32.
+template <int BM, int BN, bool A_KC, bool B_KC, bool DIRECT>
+__global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
+{
+    constexpr int FM = BM / 64, FN = BN / 64;          // fragments per wave tile
+    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // ---- block -> tile.  Workgroups are dealt round-robin to the 8 XCDs, each with
+    // its own L2: relabel so that one XCD gets a contiguous run of tile ids, and walk
+    // the tiles in bands of GM tile-rows so that a run shares A and B panels.
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const int nb = tiles_m * tiles_n;
+    int lid;
+    {
+        const int bid = blockIdx.x, per = nb >> 3, rem = nb & 7;
+        const int xcd = bid & 7, idx = bid >> 3;
+        lid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+    }
+    int tm, tn;
+    {
+        constexpr int GM = 8;
+        const int band = lid / (GM * tiles_n);
+        const int first = band * GM;
+        const int rows = tiles_m - first < GM ? tiles_m - first : GM;
+        const int in_band = lid - band * GM * tiles_n;
+        tm = first + in_band % rows;
+        tn = in_band / rows;
+    }
+    const int row0 = tm * BM, col0 = tn * BN;
+
+    // ---- K range of this block (split over gridDim.z in whole stages)
+    const int kt_per_panel = (g.Kp + BK - 1) / BK;
+    const int kt_total = g.q * kt_per_panel;
+    int kt_begin = 0, kt_end = kt_total;
+    if (g.splits > 1) {
+        const int z = blockIdx.z;
+        const int base = kt_total / g.splits, extra = kt_total % g.splits;
+        kt_begin = z * base + (z < extra ? z : extra);
+        kt_end = kt_begin + base + (z < extra ? 1 : 0);
+    }
+
+    TileLoader<BM, A_KC, DIRECT> la;
+    TileLoader<BN, B_KC, DIRECT> lb;
+    la.init(tid, row0, g.M, g.lda);
+    lb.init(tid, col0, g.N, g.ldb);
+    FragReader<BM, A_KC> ra;
+    FragReader<BN, B_KC> rb;
+    ra.init(lane, wm * (BM / 2));
+    rb.init(lane, wn * (BN / 2));
+
+    floatx16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // byte advance of one stage along K for each operand
+    const int64_t a_kstep = A_KC ? (int64_t)BK * 2 : (int64_t)BK * g.lda * 2;
+    const int64_t b_kstep = B_KC ? (int64_t)BK * 2 : (int64_t)BK * g.ldb * 2;
+
+    auto issue = [&](int kt, int stage) {
+        const int t = kt / kt_per_panel, ks = kt - t * kt_per_panel;
+        const char* ap = (const char*)g.a[t] + ks * a_kstep;
+        const char* bp = (const char*)g.b[t] + ks * b_kstep;
+        char* sa = lds + stage * STAGE_BYTES;
+        const int krem = g.Kp - ks * BK;
+        la.issue(ap, sa, tid, krem);
+        lb.issue(bp, sa + A_BYTES, tid, krem);
+    };
+    auto commit = [&](int stage) {
+        char* sa = lds + stage * STAGE_BYTES;
+        la.commit(sa, tid);
+        lb.commit(sa + A_BYTES, tid);
+    };
+
+    if (kt_begin < kt_end) {
+        issue(kt_begin, 0);
+        commit(0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+        const int cur = (kt - kt_begin) & 1;
+        const bool more = kt + 1 < kt_end;
+        if (more) issue(kt + 1, cur ^ 1);
+        const char* sa = lds + cur * STAGE_BYTES;
+        const char* sb = sa + A_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[FM], bfr[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) af[i] = ra.read(sa, i, kk);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) bfr[j] = rb.read(sb, j, kk);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) commit(cur ^ 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+
+    // ---- epilogue
+    if (g.splits > 1) {
+        // partial sums in accumulator order: [(z*nb + tile)][wave][frag][reg][lane]
+        float* w = g.ws + ((size_t)blockIdx.z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
+                   (size_t)wave * (FM * FN * 16 * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) w[((i * FN + j) * 16 + r) * 64] = acc[i][j][r];
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int col = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
+        if (col >= g.N) continue;
+        const float bv = g.bias ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col]) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row < g.M) store_out(g, row, col, acc[i][j][r], bv);
+            }
+        }
+    }
+}
+
+// Sums the K-split partials in ascending split order and applies the epilogue.
+template <int BM, int BN>
+__global__ __launch_bounds__(NTHREADS) void tess_splitk_reduce_kernel(GemmArgs g)
+{
+    constexpr int FM = BM / 64, FN = BN / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tiles_n = (g.N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
+    const int nb = tiles_m * tiles_n;
+    const int tile = blockIdx.x;
+    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    const int row0 = tm * BM, col0 = tn * BN;
+    const float* w0 = g.ws + (size_t)tile * (BM * BN) + (size_t)wave * (FM * FN * 16 * 64) + lane;
+    for (int j = 0; j < FN; ++j) {
+        const int col = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
+        const float bv = (g.bias && col < g.N) ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col]) : 0.0f;
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll 4
+            for (int r = 0; r < 16; ++r) {
+                float sum = 0.0f;
+                for (int z = 0; z < g.splits; ++z)
+                    sum += w0[(size_t)z * nb * (BM * BN) + ((i * FN + j) * 16 + r) * 64];
+                const int row = row0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row < g.M && col < g.N) store_out(g, row, col, sum, bv);
+            }
+        }
+    }
+}
+
+template <int BM, int BN, bool A_KC, bool B_KC, bool DIRECT>
+static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
+{
+    constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
+    auto kern = tess_mfma_kernel<BM, BN, A_KC, B_KC, DIRECT>;
+    static bool attr_set = false;   // per instantiation; the attribute is idempotent
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+    GemmArgs a = g;
+    a.splits = p.splits;
+    hipLaunchKernelGGL(kern, dim3(tiles, 1, p.splits), dim3(NTHREADS), lds_bytes, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (p.splits > 1) {
+        hipLaunchKernelGGL((tess_splitk_reduce_kernel<BM, BN>), dim3(tiles), dim3(NTHREADS), 0, s, a);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+template <int BM, int BN, bool DIRECT>
+static hipError_t launch_layout(const GemmArgs& g, const Plan& p, hipStream_t s)
+{
+    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, true, false, DIRECT>(g, p, s);
+    if (g.a_kc && g.b_kc) return launch_one<BM, BN, true, true, DIRECT>(g, p, s);
+    if (!g.a_kc && !g.b_kc) return launch_one<BM, BN, false, false, DIRECT>(g, p, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s)
+{
+    if (p.bm == 256 && p.bn == 256)
+        return p.direct ? launch_layout<256, 256, true>(g, p, s) : launch_layout<256, 256, false>(g, p, s);
+    if (p.bm == 128 && p.bn == 128)
+        return p.direct ? launch_layout<128, 128, true>(g, p, s) : launch_layout<128, 128, false>(g, p, s);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace tess

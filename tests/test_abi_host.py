@@ -1,0 +1,117 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before any HIP call (so this runs on
+a machine without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2105_14500_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tesseract.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tess_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = _declared_symbols()
+    assert set(B.EXPORTS) == set(names)
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_version_and_status_strings():
+    assert re.match(r"^\d+\.\d+$", B.version())
+    assert B.status_string(0) == "TESS_OK"
+    assert B.status_string(2) == "TESS_ERR_GRID"
+    assert B.status_string(99).startswith("TESS_ERR")
+
+
+def test_descriptor_rules():
+    ok = B.make_desc(2, 2, 1, 1, 1, 8, 4, 6)
+    assert B.desc_check(ok) == 0
+    assert B.block_shape(ok) == (2, 2, 3)
+    assert B.desc_check(B.make_desc(2, 3, 0, 0, 0, 12, 4, 6)) == 2      # d > q
+    assert B.desc_check(B.make_desc(0, 1, 0, 0, 0, 8, 4, 6)) == 2
+    assert B.desc_check(B.make_desc(17, 1, 0, 0, 0, 17, 17, 17)) == 2   # q > TESS_MAX_Q
+    assert B.desc_check(B.make_desc(2, 2, 2, 0, 0, 8, 4, 6)) == 2       # i outside
+    assert B.desc_check(B.make_desc(2, 2, 0, 0, 2, 8, 4, 6)) == 2       # k outside
+    assert B.desc_check(B.make_desc(2, 2, 0, 0, 0, 6, 4, 6)) == 3       # a % (q d)
+    assert B.desc_check(B.make_desc(2, 2, 0, 0, 0, 8, 3, 6)) == 3
+    assert B.desc_check(B.make_desc(2, 2, 0, 0, 0, 8, 4, 5)) == 3
+    assert B.desc_check(B.make_desc(2, 2, 0, 0, 0, 8, 4, 6, 5, 0)) == 5  # dtype
+    assert B.lib().tess_desc_check(None) == 1
+
+
+def test_entry_points_validate_before_touching_the_gpu():
+    """Bad arguments must come back as status codes without a GPU present."""
+    L = B.lib()
+    d = B.make_desc(2, 2, 0, 0, 0, 8, 4, 6)
+    fake = ctypes.c_void_p(0x1000)        # never dereferenced: validation fails first
+    two = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    holes = (ctypes.c_void_p * 2)(0x1000, None)
+    ref = ctypes.byref
+    # null descriptor / panel arrays / a hole in the panel array / null output
+    assert L.tess_linear_fwd(None, two, 2, two, 3, None, 0, fake, 3, None, None, 0, None) == 1
+    assert L.tess_linear_fwd(ref(d), None, 2, two, 3, None, 0, fake, 3, None, None, 0, None) == 1
+    assert L.tess_linear_fwd(ref(d), holes, 2, two, 3, None, 0, fake, 3, None, None, 0, None) == 1
+    assert L.tess_linear_fwd(ref(d), two, 2, two, 3, None, 0, None, 3, None, None, 0, None) == 1
+    # leading dimensions shorter than a row
+    assert L.tess_linear_fwd(ref(d), two, 1, two, 3, None, 0, fake, 3, None, None, 0, None) == 3
+    assert L.tess_linear_fwd(ref(d), two, 2, two, 2, None, 0, fake, 3, None, None, 0, None) == 3
+    assert L.tess_linear_fwd(ref(d), two, 2, two, 3, None, 0, fake, 2, None, None, 0, None) == 3
+    # unknown activation
+    assert L.tess_linear_fwd(ref(d), two, 2, two, 3, None, 9, fake, 3, None, None, 0, None) == 5
+    # dX / dW
+    assert L.tess_linear_bwd_dx(ref(d), two, 2, two, 3, fake, 2, None, 0, None) == 3   # lddy < n
+    assert L.tess_linear_bwd_dx(ref(d), two, 3, two, 3, None, 2, None, 0, None) == 1
+    assert L.tess_linear_bwd_dw(ref(d), two, 2, two, 3, fake, 3, 2, None, 0, None) == 5  # accumulate
+    assert L.tess_linear_bwd_dw(ref(d), two, 1, two, 3, fake, 3, 0, None, 0, None) == 3
+    bad = B.make_desc(2, 3, 0, 0, 0, 12, 4, 6)
+    assert L.tess_linear_bwd_dw(ref(bad), two, 2, two, 3, fake, 3, 0, None, 0, None) == 2
+
+
+def test_workspace_query_and_enforcement():
+    # a long-K, small-output bf16 problem needs split-K scratch
+    d = B.make_desc(8, 2, 0, 0, 0, 2048 * 16, 6144 * 8, 1536 * 8, B.BF16, B.BF16)
+    need = B.workspace_bytes(d, B.OP_FWD)
+    assert need > 0 and need % 4 == 0
+    assert B.workspace_bytes(d, 7) == 0
+    # fp32 problems use the plain kernel: no scratch
+    d32 = B.make_desc(2, 1, 0, 0, 0, 256, 256, 1024, B.F32, B.F32)
+    assert [B.workspace_bytes(d32, op) for op in (0, 1, 2)] == [0, 0, 0]
+    L = B.lib()
+    q = 8
+    arr = (ctypes.c_void_p * q)(*[0x10000 * (t + 1) for t in range(q)])
+    fake = ctypes.c_void_p(0x1000)
+    st = L.tess_linear_fwd(ctypes.byref(d), arr, 6144, arr, 1536, None, 0, fake, 1536, None,
+                           None, 0, None)
+    assert st == 6
+    st = L.tess_linear_fwd(ctypes.byref(d), arr, 6144, arr, 1536, None, 0, fake, 1536, None,
+                           ctypes.c_void_p(0x100000), need - 1, None)
+    assert st == 6
+
+
+def test_partition_helpers_match_block_table():
+    """Views produced for processor (i,j,k) are the blocks of the hand-written table
+    tests/golden/partition_q2_d2.txt (Alg. 3, h = i + k*q)."""
+    import torch
+    from paper_2105_14500_amd import partition as P
+    A = torch.tensor([[10.0 * r + u for u in range(4)] for r in range(8)])
+    with open(os.path.join(ROOT, "tests", "golden", "partition_q2_d2.txt")) as f:
+        rows = [l.split("|") for l in f if l.strip() and not l.startswith("#")]
+    assert len(rows) == 8
+    for left, right in rows:
+        i, j, k = (int(v) for v in left.split())
+        want = torch.tensor([float(v) for v in right.split()]).reshape(2, 2)
+        assert torch.equal(P.out_block(A, 2, 2, i, j, k), want)
+        a_p, _ = P.fwd_panels(A, torch.eye(4), 2, 2, i, j, k)
+        assert torch.equal(a_p[j], want)
+    with pytest.raises(ValueError):
+        P.block_dims(2, 3, 12, 4, 4)

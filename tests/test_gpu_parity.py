@@ -1,0 +1,153 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU fp64 oracle,
+element by element on the same seeded inputs.  Sizes span several tiles and
+ragged tails and are small enough for the oracle to finish in seconds; the
+full-size configurations are in test_gpu_configs.py."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import tess_workloads as wl
+import paper_2105_14500_amd as tess
+from paper_2105_14500_amd import binding as B, partition as P
+from oracle import tess_oracle as orc
+from gpu_util import TOL, f64, dev, run_share, oracle_share, rel_err, workspace, code, tdtype
+
+pytestmark = pytest.mark.gpu
+
+
+# (q, d, m, kb, n, dtype): what each shape exercises
+SHAPES = [
+    (2, 1, 256, 128, 256, "bf16"),    # direct 128x128 tiles, fwd split
+    (2, 2, 512, 256, 512, "bf16"),    # several 128-tiles per side
+    (3, 2, 200, 72, 136, "bf16"),     # ragged M/N/K tails, register-staged loader
+    (2, 2, 264, 64, 520, "bf16"),     # K % 64 == 0 (direct), ragged M and N
+    (1, 1, 128, 192, 128, "bf16"),    # q = d = 1: plain matmul
+    (4, 3, 40, 8, 16, "bf16"),        # tiny: one partial tile
+    (2, 2, 33, 17, 29, "bf16"),       # no 8-alignment: generic kernel, bf16 inputs
+    (2, 2, 130, 70, 100, "f32"),      # fp32 generic kernel, ragged
+    (3, 1, 64, 64, 64, "f32"),
+    (2, 2, 1024, 1024, 1024, "bf16"),  # 256x256 tiles
+    (2, 1, 2048, 256, 2048, "bf16"),   # 256x256 tiles, many of them
+]
+
+
+@pytest.mark.parametrize("q,d,m,kb,n,dtype", SHAPES)
+def test_share_matches_oracle(q, d, m, kb, n, dtype):
+    inp = wl.share_inputs(q, m, kb, n, dtype=dtype, seed=1234 + m + kb + n, w_std=0.05)
+    got = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], dtype, dtype,
+                    act="gelu_erf", want_preact=True)
+    want = oracle_share(inp["x"], inp["w"], inp["bias"], inp["dy"], act="gelu_erf")
+    for key in ("y", "preact", "dx", "dw"):
+        e = rel_err(got[key], want[key])
+        assert e <= TOL[dtype], (key, e)
+
+
+@pytest.mark.parametrize("q,d,m,kb,n,dtype", SHAPES)
+def test_small_integers_are_bit_exact(q, d, m, kb, n, dtype):
+    """Inputs in {-2..2}: every product and partial sum is exactly representable
+    in fp32, so the fp32 outputs must equal the oracle bit for bit."""
+    inp = wl.share_inputs(q, m, kb, n, dtype=dtype, seed=99, integers=True)
+    got = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], dtype, "f32", act="none")
+    want = oracle_share(inp["x"], inp["w"], inp["bias"], inp["dy"], act="none")
+    for key in ("y", "dx", "dw"):
+        assert np.array_equal(f64(got[key]), want[key]), key
+
+
+@pytest.mark.parametrize("act", ["none", "gelu_erf", "gelu_tanh"])
+@pytest.mark.parametrize("dtype,shape", [("bf16", (2, 2, 256, 128, 384)), ("f32", (2, 2, 96, 80, 72))])
+def test_epilogue_forms(act, dtype, shape):
+    q, d, m, kb, n = shape
+    inp = wl.share_inputs(q, m, kb, n, dtype=dtype, seed=7, w_std=0.1, bias_std=0.5)
+    got = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], dtype, "f32", act=act,
+                    want_preact=True)
+    xs = [f64(inp["x"][t]) for t in range(q)]
+    ws = [f64(inp["w"][t]) for t in range(q)]
+    oact = {"none": orc.ACT_NONE, "gelu_erf": orc.ACT_GELU_ERF, "gelu_tanh": orc.ACT_GELU_TANH}[act]
+    y, z = orc.fwd_panels(xs, ws, bias=f64(inp["bias"]), act=oact, want_z=True)
+    # fp32 outputs: only accumulation-order and erf/tanh rounding remain
+    assert rel_err(got["y"], y) <= 1e-5
+    assert rel_err(got["preact"], z) <= 1e-5
+    # no bias pointer == zero bias
+    got0 = run_share(q, d, inp["x"], inp["w"], None, inp["dy"], dtype, "f32", act=act)
+    y0 = orc.fwd_panels(xs, ws, bias=None, act=oact)
+    assert rel_err(got0["y"], y0) <= 1e-5
+
+
+def test_bf16_output_is_rne_of_fp32_result():
+    """Down-cast decision taken in the kernel's precision: the bf16 output must be
+    the round-to-nearest-even of the same kernel's fp32 output."""
+    q, d, m, kb, n = 2, 2, 256, 128, 256
+    inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=5, w_std=0.1)
+    g32 = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "f32", act="gelu_erf")
+    g16 = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "bf16", act="gelu_erf")
+    for key in ("y", "dx", "dw"):
+        want = orc.round_bf16(g32[key].numpy())
+        assert np.array_equal(f64(g16[key]), want), key
+
+
+@pytest.mark.parametrize("dtype,dims", [("bf16", (2, 2, 128, 64, 128)), ("bf16", (3, 3, 24, 40, 56)),
+                                        ("f32", (2, 2, 20, 12, 28))])
+def test_full_grid_emulation_small(dtype, dims):
+    """Every processor of the grid on strided views of the global matrices; the
+    reassembled C, dX and the depth-summed dW equal the unpartitioned products."""
+    q, d, m, kb, n = dims
+    a, b, c = m * q * d, kb * q, n * q
+    X, W, bias, dY = wl.full_grid_inputs(a, b, c, dtype=dtype, seed=3, bias_std=0.02, w_std=0.05)
+    Xd, Wd, bd, dYd = dev(X), dev(W), dev(bias), dev(dY)
+    odt = tdtype(dtype)
+    Y = torch.full((a, c), float("nan"), dtype=odt, device="cuda:0")
+    dX = torch.full((a, b), float("nan"), dtype=odt, device="cuda:0")
+    dW = torch.zeros((b, c), dtype=torch.float32, device="cuda:0")
+    for i, j, k in itertools.product(range(q), range(q), range(d)):
+        desc = B.make_desc(q, d, i, j, k, a, b, c, code(dtype), code(dtype))
+        a_p, b_p = P.fwd_panels(Xd, Wd, q, d, i, j, k)
+        tess.linear_fwd(desc, a_p, b_p, bd[j * n:(j + 1) * n], B.ACT_NONE,
+                        P.out_block(Y, q, d, i, j, k), workspace=workspace(desc, B.OP_FWD))
+        dy_p, w_p = P.dx_panels(dYd, Wd, q, d, i, j, k)
+        tess.linear_bwd_dx(desc, dy_p, w_p, P.out_block(dX, q, d, i, j, k),
+                           workspace=workspace(desc, B.OP_BWD_DX))
+        x_p, dy2_p = P.dw_panels(Xd, dYd, q, d, i, j, k)
+        tess.linear_bwd_dw(desc, x_p, dy2_p, P.weight_block(dW, q, i, j), accumulate=True,
+                           workspace=workspace(desc, B.OP_BWD_DW))
+    torch.cuda.synchronize()
+    X64, W64, dY64 = f64(X), f64(W), f64(dY)
+    assert rel_err(Y, orc.matmul_nn(X64, W64) + f64(bias)[None, :]) <= TOL[dtype]
+    assert rel_err(dX, orc.matmul_nt(dY64, W64)) <= TOL[dtype]
+    assert rel_err(dW, orc.matmul_tn(X64, dY64)) <= (1e-5 if dtype == "f32" else 1e-4)
+
+
+def test_dw_depth_accumulation_order():
+    """d calls with accumulate=1, k ascending, into one fp32 buffer."""
+    q, d, m, kb, n = 2, 2, 192, 128, 256
+    acc = torch.zeros((kb, n), dtype=torch.float32, device="cuda:0")
+    want = np.zeros((kb, n))
+    for k in range(d):
+        inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=50 + k)
+        run_share(q, d, inp["x"], inp["w"], None, inp["dy"], "bf16", "bf16", dw_accumulate_into=acc)
+        orc.bwd_dw_panels([f64(inp["x"][t]) for t in range(q)], [f64(inp["dy"][t]) for t in range(q)],
+                          accumulate_into=want)
+    assert rel_err(acc, want) <= 1e-5
+
+
+def test_run_to_run_determinism():
+    q, d, m, kb, n = 4, 2, 256, 512, 256     # split-K path
+    inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=8)
+    r1 = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "f32", act="gelu_erf")
+    r2 = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "f32", act="gelu_erf")
+    for key in ("y", "dx", "dw"):
+        assert torch.equal(r1[key], r2[key]), key
+
+
+def test_empty_and_error_paths_leave_outputs_untouched():
+    q, d, m, kb, n = 2, 2, 64, 64, 64
+    inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=1)
+    xd, wd = dev(inp["x"]), dev(inp["w"])
+    y = torch.full((m, n), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    bad = B.make_desc(q, 3, 0, 0, 0, m * q * 3, kb * q, n * q, B.BF16, B.BF16)   # d > q
+    with pytest.raises(tess.TessError) as ei:
+        tess.linear_fwd(bad, list(xd), list(wd), None, B.ACT_NONE, y)
+    assert ei.value.status == 2
+    torch.cuda.synchronize()
+    assert torch.all(y == 7.0)
