@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the Tesseract per-processor linear hot path on one MI355X.
+
+A step is one pass of the whole hot path over one processor's share of a
+workload: for every linear layer of the workload, forward (bias/GELU epilogue
+fused), input gradient and the depth-slice weight gradient accumulated into an
+fp32 buffer.  Inputs are seeded synthetic panels, resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16 MFMA, "2.5 PFLOP/s")
+DEFAULT_WORKLOAD = "cfg4_q4d4_bf16_attn_h8192"   # the largest per-processor block shapes
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--all", action="store_true", help="also time every other bf16 workload")
+    ap.add_argument("--kernel-reps", type=int, default=10)
+    return ap.parse_args()
+
+
+class LayerState:
+    """Device buffers of one layer of one processor's share (packed panels)."""
+
+    def __init__(self, torch, tess, B, wl, w, L, seed, sets):
+        self.L = L
+        self.q, self.d = w.q, w.d
+        self.desc = B.make_desc(w.q, w.d, 0, 0, 0, L.a, L.b, L.c, B.BF16, B.BF16)
+        self.act = {"none": B.ACT_NONE, "gelu_erf": B.ACT_GELU_ERF}[L.act]
+        self.flops_call = 2.0 * L.m * L.kb * L.n * w.q          # 2abc/p
+        self.sets = []
+        self.host = None
+        for s in range(sets):
+            inp = wl.share_inputs(w.q, L.m, L.kb, L.n, dtype="bf16", seed=seed + s,
+                                  bias_std=L.bias_std)
+            if s == 0:
+                self.host = inp
+            dev = {k: v.to("cuda:0") for k, v in inp.items()}
+            dev["y"] = torch.empty((L.m, L.n), dtype=torch.bfloat16, device="cuda:0")
+            dev["dx"] = torch.empty((L.m, L.kb), dtype=torch.bfloat16, device="cuda:0")
+            dev["dw"] = torch.zeros((L.kb, L.n), dtype=torch.float32, device="cuda:0")
+            dev["xl"], dev["wl"], dev["dyl"] = list(dev["x"]), list(dev["w"]), list(dev["dy"])
+            self.sets.append(dev)
+        nbytes = max(tess.workspace_bytes(self.desc, op) for op in (0, 1, 2))
+        self.ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device="cuda:0")
+        self.tess = tess
+
+    def fwd(self, s):
+        b = self.sets[s % len(self.sets)]
+        self.tess.linear_fwd(self.desc, b["xl"], b["wl"], b["bias"], self.act, b["y"],
+                             workspace=self.ws)
+
+    def dx(self, s):
+        b = self.sets[s % len(self.sets)]
+        self.tess.linear_bwd_dx(self.desc, b["dyl"], b["wl"], b["dx"], workspace=self.ws)
+
+    def dw(self, s):
+        b = self.sets[s % len(self.sets)]
+        self.tess.linear_bwd_dw(self.desc, b["xl"], b["dyl"], b["dw"], accumulate=True,
+                                workspace=self.ws)
+
+
+def time_workload(torch, tess, B, wl, w, steps, warmup, kernel_reps):
+    layers = []
+    for li, L in enumerate(w.layers):
+        per_set = 2 * w.q * (L.m * L.kb + L.kb * L.n + L.m * L.n) + 2 * (L.m * L.n + L.m * L.kb) \
+            + 4 * L.kb * L.n
+        sets = 1 if per_set >= 400e6 else max(2, int(600e6 // per_set))
+        layers.append(LayerState(torch, tess, B, wl, w, L, seed=1000 * li, sets=min(sets, 8)))
+
+    def step(s):
+        for st in layers:
+            st.fwd(s)
+            st.dx(s)
+            st.dw(s)
+
+    for s in range(warmup):
+        step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        step(s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    flops_step = sum(3.0 * st.flops_call for st in layers)
+    ms_step = dt / steps * 1e3
+
+    # per-call timing with HIP events on the launch stream
+    calls = {}
+    for st in layers:
+        for name in ("fwd", "dx", "dw"):
+            fn = getattr(st, name)
+            fn(0)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for s in range(kernel_reps):
+                fn(s)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / kernel_reps
+            M, N, K = {"fwd": (st.L.m, st.L.n, st.L.kb * w.q), "dx": (st.L.m, st.L.kb, st.L.n * w.q),
+                       "dw": (st.L.kb, st.L.n, st.L.m * w.q)}[name]
+            calls[f"{st.L.name}.{name}"] = {"MxNxK": f"{M}x{N}x{K}", "ms": round(ms, 4),
+                                            "tflops": round(st.flops_call / ms / 1e9, 1),
+                                            "frac_peak": round(st.flops_call / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    return {"ms_per_step": ms_step, "tflops": flops_step / ms_step / 1e9, "calls": calls,
+            "flops_step": flops_step, "layers": layers}
+
+
+def cpu_baseline(torch, w, layer_state, budget_s=18.0):
+    """The fp64 oracle as it stands, on a bounded sample of the first layer's calls:
+    a subset of output rows (and, for dW, a window of columns) of the same panels."""
+    import numpy as np
+    from oracle import tess_oracle as orc
+    L, q = layer_state.L, w.q
+    host = layer_state.host
+
+    def f64(t):
+        return t.to(torch.float64).numpy()
+
+    cols = min(L.n, 1024)
+    ws = [f64(host["w"][t]) for t in range(q)]
+    dyw = [f64(host["dy"][t][:, :cols]) for t in range(q)]
+
+    def run(rows_fwd, rows_dx, rows_dw):
+        rf = np.linspace(0, L.m - 1, rows_fwd).astype(np.int64)
+        rx = np.linspace(0, L.m - 1, rows_dx).astype(np.int64)
+        rw = np.linspace(0, L.kb - 1, rows_dw).astype(np.int64)
+        xs = [f64(host["x"][t][rf]) for t in range(q)]
+        dys = [f64(host["dy"][t][rx]) for t in range(q)]
+        xcols = [np.ascontiguousarray(f64(host["x"][t][:, rw])) for t in range(q)]
+        t0 = time.perf_counter()
+        orc.fwd_panels(xs, ws, bias=f64(host["bias"]), act=orc.ACT_GELU_ERF if L.act == "gelu_erf" else 0)
+        orc.bwd_dx_panels(dys, ws)
+        orc.bwd_dw_panels(xcols, dyw)
+        dt = time.perf_counter() - t0
+        fl = 2.0 * q * L.kb * L.n * (rows_fwd + rows_dx) + 2.0 * q * L.m * cols * rows_dw
+        return fl, dt
+
+    fl, dt = run(8, 8, 8)                      # calibration
+    rate = fl / dt
+    per_row = 2.0 * q * L.kb * L.n
+    rows = int(max(8, min(L.m, budget_s / 3 * rate / per_row)))
+    rows_dw = int(max(8, min(L.kb, budget_s / 3 * rate / (2.0 * q * L.m * cols))))
+    fl, dt = run(rows, rows, rows_dw)
+    return {"value": round(fl / dt / 1e12, 6), "unit": "TFLOP/s", "cores": orc.num_threads(),
+            "kind": "oracle",
+            "sample": f"{w.name}/{L.name}: fwd and dX on {rows} evenly spaced output rows "
+                      f"(all columns), dW on {rows_dw} output rows x first {cols} columns; "
+                      f"{fl / 1e9:.1f} GFLOP in {dt:.1f} s, fp64"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one processor's share on ONE GPU; "
+              "--gpus N with N > 1 is not supported (no collectives are part of it).",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import tess_workloads as wl
+    import paper_2105_14500_amd as tess
+    from paper_2105_14500_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    tess.binding.lib()   # fail loudly when the HIP library is missing
+    w = wl.workload_by_name(args.workload)
+    if w is None or w.dtype != "bf16":
+        print(f"unknown bf16 workload {args.workload}", file=sys.stderr)
+        sys.exit(2)
+
+    res = time_workload(torch, tess, B, wl, w, args.steps, args.warmup, args.kernel_reps)
+    # dominant kernel = the call with the largest time per step
+    dom_name, dom = max(res["calls"].items(), key=lambda kv: kv[1]["ms"])
+    dom_layer = next(st for st in res["layers"] if dom_name.startswith(st.L.name + "."))
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"{w.name}/{dom_name}")
+    out = {
+        "metric": "TFLOP/s and % of bf16 MFMA peak, Tesseract linear fwd+bwd, 1 MI355X",
+        "value": round(res["tflops"], 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(res["ms_per_step"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "pct_of_bf16_mfma_peak": round(100.0 * res["tflops"] / PEAK_BF16_TFLOPS, 2),
+        "config": {"workload": w.name, "grid": [w.q, w.q, w.d], "processor": [0, 0, 0],
+                   "layers": {L.name: {"a": L.a, "b": L.b, "c": L.c, "block": [L.m, L.kb, L.n],
+                                       "epilogue": L.act} for L in w.layers},
+                   "step": "per layer: fwd + dX + dW(accumulate fp32)",
+                   "flop_per_step": res["flops_step"]},
+        "calls": res["calls"],
+        "roofline": {"bound": "mfma", "kernel": dom_name,
+                     "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4),
+                     "flop_per_launch": dom_layer.flops_call, "avg_ms": dom["ms"],
+                     "traffic": traffic},
+    }
+    layers0 = res["layers"]
+    if args.all:
+        others = {}
+        del res
+        for ow in wl.WORKLOADS:
+            if ow.dtype != "bf16" or ow.name == w.name:
+                continue
+            torch.cuda.empty_cache()
+            r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, args.kernel_reps)
+            others[ow.name] = {"tflops": round(r["tflops"], 2),
+                               "pct_peak": round(100.0 * r["tflops"] / PEAK_BF16_TFLOPS, 2),
+                               "ms_per_step": round(r["ms_per_step"], 4), "calls": r["calls"]}
+            del r
+        out["other_workloads"] = others
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(torch, w, layers0[0])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -3,6 +3,8 @@
 // kernel/tile/split selection.  No HIP call happens before validation has passed.
 #include "tess_internal.h"
 
+#include <stdlib.h>
+
 namespace tess {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -13,6 +15,7 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
     Plan p{};
     p.path = Path::Generic;
     p.bm = p.bn = 0;
+    p.bk = 64;
     p.splits = 1;
     p.direct = 0;
     p.ws_bytes = 0;
@@ -22,7 +25,9 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
     // otherwise 128 x 128
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
     const int64_t kt_total = (int64_t)q * ((Kp + BK_HOST - 1) / BK_HOST);
-    if (M >= 256 && N >= 256 && t256 * (kt_total >= 8 ? 8 : 1) >= 192) {
+    p.direct = (Kp % BK_HOST == 0) ? 1 : 0;
+    // the register-staged loader (ragged K) only exists for the small tile
+    if (p.direct && M >= 256 && N >= 256 && t256 * (kt_total >= 8 ? 8 : 1) >= 192) {
         p.bm = p.bn = 256;
     } else {
         p.bm = p.bn = 128;
@@ -38,7 +43,7 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
         if (splits < 1) splits = 1;
     }
     p.splits = splits;
-    p.direct = (Kp % BK_HOST == 0) ? 1 : 0;
+    if (const char* e = getenv("TESS_BK")) p.bk = atoi(e) == 32 ? 32 : 64;   // tuning knob
     if (splits > 1) p.ws_bytes = (size_t)splits * tiles * p.bm * p.bn * sizeof(float);
     return p;
 }

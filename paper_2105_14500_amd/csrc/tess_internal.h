@@ -45,6 +45,7 @@ enum class Path : int32_t { Generic = 0, Mfma = 1 };
 struct Plan {
     Path path;
     int32_t bm, bn;     // macro tile of the MFMA path
+    int32_t bk;         // K extent of one LDS stage (64, or 32 with a deeper ring)
     int32_t splits;     // K splits (1 = none)
     int32_t direct;     // 1: global->LDS direct loads (needs Kp % 64 == 0)
     size_t ws_bytes;

@@ -8,6 +8,8 @@
 //   * tess_generic_kernel  any shape / alignment / fp32 inputs, fp32 FMA.
 #include "tess_internal.h"
 
+#include <type_traits>
+
 namespace tess {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -19,7 +21,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 #define GLB_PTR(T) __attribute__((address_space(1))) T*
 
-constexpr int BK = 64;          // K extent of one LDS stage (bf16 elements)
 constexpr int NTHREADS = 256;   // 4 wavefronts, arranged 2 x 2 over the macro tile
 
 // ---------------------------------------------------------------------------
@@ -151,62 +152,96 @@ hipError_t launch_generic(const GemmArgs& g, hipStream_t s)
 // ---------------------------------------------------------------------------
 // MFMA path
 // ---------------------------------------------------------------------------
-// LDS tile formats, in 16-byte granules (8 bf16):
-//  KC operand, R rows x 64 k:  granule (r, pc) at index r*8 + pc holds k-chunk
+// LDS tile formats, in 16-byte granules (8 bf16), for a stage of BK contracted
+// elements (CH = BK/8 granules along k):
+//  KC operand, R rows x BK k:  granule (r, pc) at index r*CH + pc holds k-chunk
 //      c = pc ^ swz_kc(r) of row r.  A 32x32x16 fragment read (lane -> row l%32,
 //      chunk 2*kk + l/32, one 128-bit read) then touches every bank once per
 //      16 consecutive rows.
-//  MC operand, 64 k-rows x R elements: granule (kr, pg) at index kr*(R/8) + pg
+//  MC operand, BK k-rows x R elements: granule (kr, pg) at index kr*(R/8) + pg
 //      holds elements 8g..8g+7, g = pg ^ swz_mc(kr), of k-row kr.  Fragments are
 //      read with the transposing 64-bit LDS read, which hands lane s of a 16-lane
 //      group the 4 k-values of column s from 4 k-rows.
 // Tiles are always written linearly (granule index = it*256 + thread), so the
 // swizzle is applied on the global-memory side of the copy.
-__device__ __forceinline__ int swz_kc(int r) { return (r >> 1) & 7; }
+template <int BK>
+__device__ __forceinline__ int swz_kc(int r)
+{
+    constexpr int CH = BK / 8, RPL = 128 / BK;   // chunks per row, rows per 256-byte bank line
+    return (r / RPL) % CH;
+}
 __device__ __forceinline__ int swz_mc(int kr) { return ((kr & 3) << 2) ^ (((kr >> 3) & 1) << 1); }
 
-template <int R, bool KC, bool DIRECT>
+// Compile-time loop: the body sees the index as an integral constant, so every
+// accumulator index is static and the accumulators stay in registers.
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Workgroup barrier that orders LDS traffic only: global loads into LDS that are
+// still in flight for later stages are not waited for.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <int R, int BK, bool KC, bool DIRECT>
 struct TileLoader {
-    static constexpr int NG = R * 8;             // granules per stage
+    static constexpr int CH = BK / 8;            // granules per row (KC)
+    static constexpr int NG = R * CH;            // granules per stage
     static constexpr int ITERS = NG / NTHREADS;
     static constexpr int RG = R / 8;             // granules per k-row (MC)
     uint32_t off[ITERS];    // byte offset of this thread's granule inside a panel at k0 = 0
-    uint32_t kpos[ITERS];   // k index (within the 64-wide stage) that the granule starts at
+    uint32_t kpos[DIRECT ? 1 : ITERS];   // k index (within the stage) that the granule starts at
     u32x4 stage[DIRECT ? 1 : ITERS];
 
     // origin: first row (KC) / first element along R (MC) of this block's tile;
     // extent: total rows / elements of the operand along R; ld in elements.
     __device__ __forceinline__ void init(int tid, int origin, int extent, int64_t ld)
     {
-#pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
+        static_for<ITERS>([&](auto it) {
             const int G = it * NTHREADS + tid;
             if (KC) {
-                const int r = G >> 3, pc = G & 7;
-                const int c = pc ^ swz_kc(r);
+                const int r = G / CH, pc = G % CH;
+                const int c = pc ^ swz_kc<BK>(r);
                 int row = origin + r;
                 row = row < extent ? row : extent - 1;
                 off[it] = (uint32_t)(((int64_t)row * ld + 8 * c) * 2);
-                kpos[it] = 8 * c;
+                if (!DIRECT) kpos[it] = 8 * c;
             } else {
                 const int kr = G / RG, pg = G % RG;
                 const int gidx = pg ^ swz_mc(kr);
                 int col = origin + 8 * gidx;
                 col = col + 8 <= extent ? col : extent - 8;
                 off[it] = (uint32_t)(((int64_t)kr * ld + col) * 2);
-                kpos[it] = kr;
+                if (!DIRECT) kpos[it] = kr;
             }
-        }
+        });
     }
 
     // base: panel pointer advanced to the stage's first k (uniform); krem: number of
     // valid k from there (only used by the staged variant, for the zero-filled tail).
-    __device__ __forceinline__ void issue(const char* base, char* lds_tile, int tid, int krem)
+    // wave_u: wavefront index as a wave-uniform value (the LDS address of a direct
+    // load is a scalar: base of the 64 granules that the wavefront's lanes fill).
+    __device__ __forceinline__ void issue(const char* base, char* lds_tile, int wave_u, int tid,
+                                          int krem)
     {
-#pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
+        static_for<ITERS>([&](auto it) {
             if (DIRECT) {
-                const int wave_first = (it * NTHREADS + (tid & ~63)) * 16;
+                const int wave_first = (it * NTHREADS + wave_u * 64) * 16;
                 __builtin_amdgcn_global_load_lds((const GLB_PTR(void))(base + off[it]),
                                                  (LDS_PTR(void))(lds_tile + wave_first), 16, 0, 0);
             } else {
@@ -214,45 +249,46 @@ struct TileLoader {
                 if ((int)kpos[it] < krem) v = *(const u32x4*)(base + off[it]);
                 stage[it] = v;
             }
-        }
+        });
     }
     __device__ __forceinline__ void commit(char* lds_tile, int tid)
     {
         if (!DIRECT) {
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it)
+            static_for<ITERS>([&](auto it) {
                 *(u32x4*)(lds_tile + (it * NTHREADS + tid) * 16) = stage[it];
+            });
         }
     }
 };
 
 // Fragment reader: 32 (rows along R) x 16 (k) bf16 operand fragment for
 // v_mfma_f32_32x32x16_bf16: lane l gets row l%32, k = 8*(l/32) .. +7.
-template <int R, bool KC>
+template <int R, int BK, bool KC>
 struct FragReader {
-    uint32_t lane_off;      // per-lane byte offset, fragment 0
-    uint32_t kcol[4];       // KC: byte offset of the k-chunk for each of the 4 k16 steps
+    static constexpr int KSTEPS = BK / 16;
+    uint32_t lane_off;          // per-lane byte offset, fragment 0
+    uint32_t kcol[KC ? KSTEPS : 2];   // KC: byte offset of the k-chunk for each k16 step
     __device__ __forceinline__ void init(int lane, int wave_origin)
     {
         if (KC) {
             const int r = wave_origin + (lane & 31);
-            lane_off = (uint32_t)r * 128u;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) kcol[kk] = (uint32_t)(((2 * kk + (lane >> 5)) ^ swz_kc(r)) * 16);
+            lane_off = (uint32_t)r * (uint32_t)(BK * 2);
+            static_for<KSTEPS>([&](auto kk) {
+                kcol[kk] = (uint32_t)(((2 * kk + (lane >> 5)) ^ swz_kc<BK>(r)) * 16);
+            });
         } else {
             const int s = lane & 15, bl = lane >> 4;
-            const int kr = 8 * (bl >> 1) + (s >> 2);           // k-row inside a k16 step, h = 0
+            const int kr = 8 * (bl >> 1) + (s >> 2);           // k-row inside a k16 step, first read
             lane_off = (uint32_t)(kr * (R / 8) * 16 + (s & 1) * 8);
             kcol[0] = (uint32_t)swz_mc(kr);
-            kcol[1] = (uint32_t)(wave_origin + 16 * (bl & 1) + 4 * (s & 3)) >> 3;  // granule of frag 0
-            kcol[2] = kcol[3] = 0;
+            kcol[1] = (uint32_t)(wave_origin + 16 * (bl & 1) + 4 * (s & 3)) >> 3;  // granule, frag 0
         }
     }
     // f: fragment index along R inside the wave tile, kk: k16 step of the stage
     __device__ __forceinline__ bf16x8 read(const char* lds_tile, int f, int kk) const
     {
         if (KC) {
-            return *(const bf16x8*)(lds_tile + lane_off + f * (32 * 128) + kcol[kk]);
+            return *(const bf16x8*)(lds_tile + lane_off + f * (32 * BK * 2) + kcol[kk]);
         } else {
             const uint32_t gsw = ((kcol[1] + 4u * f) ^ kcol[0]) * 16u;
             const char* p = lds_tile + lane_off + gsw + kk * (16 * (R / 8) * 16);
@@ -265,40 +301,90 @@ struct FragReader {
     }
 };
 
-// Accumulator layout of one 32x32 fragment: lane l, register r ->
+// Stores one 32x32 accumulator fragment.  Accumulator layout: lane l, register r ->
 //   row = 8*(r/4) + 4*(l/32) + r%4,  col = l%32.
-template <int BM, int BN, bool A_KC, bool B_KC, bool DIRECT>
+// frow0: first row of the fragment + 4*(l/32); col: this lane's column.
+__device__ __forceinline__ void store_fragment(const GemmArgs& g, const floatx16& v, int frow0,
+                                               int col, float bias_v)
+{
+    if (col >= g.N) return;
+    float z[16];
+    static_for<16>([&](auto r) { z[r] = v[r()] + bias_v; });
+    if (g.preact) {
+        static_for<16>([&](auto r) {
+            const int row = frow0 + 8 * (r / 4) + (r % 4);
+            if (row < g.M) {
+                const int64_t o = (int64_t)row * g.ldo + col;
+                if (g.out_f32) ((float*)g.preact)[o] = z[r];
+                else ((uint16_t*)g.preact)[o] = f32_to_bf16_bits(z[r]);
+            }
+        });
+    }
+    if (g.act == TESS_ACT_GELU_ERF) static_for<16>([&](auto r) { z[r] = gelu_erf_f(z[r]); });
+    else if (g.act == TESS_ACT_GELU_TANH) static_for<16>([&](auto r) { z[r] = gelu_tanh_f(z[r]); });
+    if (g.out_f32) {
+        float* out = (float*)g.out;
+        if (g.accumulate) {
+            static_for<16>([&](auto r) {
+                const int row = frow0 + 8 * (r / 4) + (r % 4);
+                if (row < g.M) out[(int64_t)row * g.ldo + col] += z[r];
+            });
+        } else {
+            static_for<16>([&](auto r) {
+                const int row = frow0 + 8 * (r / 4) + (r % 4);
+                if (row < g.M) out[(int64_t)row * g.ldo + col] = z[r];
+            });
+        }
+    } else {
+        uint16_t* out = (uint16_t*)g.out;
+        static_for<16>([&](auto r) {
+            const int row = frow0 + 8 * (r / 4) + (r % 4);
+            if (row < g.M) out[(int64_t)row * g.ldo + col] = f32_to_bf16_bits(z[r]);
+        });
+    }
+}
+
+// Block -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each with
+// its own L2: relabel so that one XCD gets a contiguous run of tile ids, and walk the
+// tiles in bands of 8 tile-rows so that a run shares A and B panels.
+__device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
+{
+    const int nb = tiles_m * tiles_n;
+    const int per = nb >> 3, rem = nb & 7;
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int lid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+    constexpr int GM = 8;
+    const int band = lid / (GM * tiles_n);
+    const int first = band * GM;
+    const int rows = tiles_m - first < GM ? tiles_m - first : GM;
+    const int in_band = lid - band * GM * tiles_n;
+    tm = first + in_band % rows;
+    tn = in_band / rows;
+}
+
+// Scheduling hints: interleave LDS reads and global->LDS loads with the MFMAs of a
+// k16 step so that the matrix pipe does not wait for operands.
+#define SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
+#define SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
+#define SCHED_VMEM(n) __builtin_amdgcn_sched_group_barrier(0x020, n, 0)
+
+template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, bool DIRECT>
 __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
 {
     constexpr int FM = BM / 64, FN = BN / 64;          // fragments per wave tile
+    constexpr int KSTEPS = BK / 16;
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static_assert(DIRECT || NSTAGE == 2, "the register-staged loader is double-buffered");
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int wm = wave >> 1, wn = wave & 1;
-
-    // ---- block -> tile.  Workgroups are dealt round-robin to the 8 XCDs, each with
-    // its own L2: relabel so that one XCD gets a contiguous run of tile ids, and walk
-    // the tiles in bands of GM tile-rows so that a run shares A and B panels.
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int nb = tiles_m * tiles_n;
-    int lid;
-    {
-        const int bid = blockIdx.x, per = nb >> 3, rem = nb & 7;
-        const int xcd = bid & 7, idx = bid >> 3;
-        lid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
-    }
     int tm, tn;
-    {
-        constexpr int GM = 8;
-        const int band = lid / (GM * tiles_n);
-        const int first = band * GM;
-        const int rows = tiles_m - first < GM ? tiles_m - first : GM;
-        const int in_band = lid - band * GM * tiles_n;
-        tm = first + in_band % rows;
-        tn = in_band / rows;
-    }
+    block_to_tile(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int row0 = tm * BM, col0 = tn * BN;
 
     // ---- K range of this block (split over gridDim.z in whole stages)
@@ -311,71 +397,155 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
         kt_begin = z * base + (z < extra ? z : extra);
         kt_end = kt_begin + base + (z < extra ? 1 : 0);
     }
+    const int nkt = kt_end - kt_begin;
 
-    TileLoader<BM, A_KC, DIRECT> la;
-    TileLoader<BN, B_KC, DIRECT> lb;
+    typedef TileLoader<BM, BK, A_KC, DIRECT> LA;
+    typedef TileLoader<BN, BK, B_KC, DIRECT> LB;
+    constexpr int LOADS = LA::ITERS + LB::ITERS;       // global loads per thread per stage
+    LA la;
+    LB lb;
     la.init(tid, row0, g.M, g.lda);
     lb.init(tid, col0, g.N, g.ldb);
-    FragReader<BM, A_KC> ra;
-    FragReader<BN, B_KC> rb;
+    FragReader<BM, BK, A_KC> ra;
+    FragReader<BN, BK, B_KC> rb;
     ra.init(lane, wm * (BM / 2));
     rb.init(lane, wn * (BN / 2));
 
-    floatx16 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    floatx16 acc[FM * FN];
+    static_for<FM * FN>([&](auto f) {
+        static_for<16>([&](auto r) { acc[f][r()] = 0.0f; });
+    });
 
     // byte advance of one stage along K for each operand
     const int64_t a_kstep = A_KC ? (int64_t)BK * 2 : (int64_t)BK * g.lda * 2;
     const int64_t b_kstep = B_KC ? (int64_t)BK * 2 : (int64_t)BK * g.ldb * 2;
 
-    auto issue = [&](int kt, int stage) {
-        const int t = kt / kt_per_panel, ks = kt - t * kt_per_panel;
-        const char* ap = (const char*)g.a[t] + ks * a_kstep;
-        const char* bp = (const char*)g.b[t] + ks * b_kstep;
+    // Panel pointers are fetched from the kernel-argument segment (constant address
+    // space, scalar loads) with the uniform step index; indexing the by-value copy
+    // of the argument struct dynamically would move it to scratch memory.
+    typedef __attribute__((address_space(4))) const GemmArgs* KernArgs;
+    const KernArgs ka = (KernArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    // (panel, stage-in-panel) of the next stage to fetch and its operand pointers,
+    // advanced incrementally; the pointers are re-read only when the panel changes
+    int ld_t = kt_begin / kt_per_panel, ld_ks = kt_begin - ld_t * kt_per_panel;
+    const char* ld_ap = (const char*)ka->a[ld_t < g.q ? ld_t : 0] + ld_ks * a_kstep;
+    const char* ld_bp = (const char*)ka->b[ld_t < g.q ? ld_t : 0] + ld_ks * b_kstep;
+    auto issue = [&](int stage) {
         char* sa = lds + stage * STAGE_BYTES;
-        const int krem = g.Kp - ks * BK;
-        la.issue(ap, sa, tid, krem);
-        lb.issue(bp, sa + A_BYTES, tid, krem);
+        const int krem = g.Kp - ld_ks * BK;
+        la.issue(ld_ap, sa, wave_u, tid, krem);
+        lb.issue(ld_bp, sa + A_BYTES, wave_u, tid, krem);
     };
-    auto commit = [&](int stage) {
-        char* sa = lds + stage * STAGE_BYTES;
-        la.commit(sa, tid);
-        lb.commit(sa + A_BYTES, tid);
+    auto advance = [&]() {
+        ld_ap += a_kstep;
+        ld_bp += b_kstep;
+        if (++ld_ks == kt_per_panel) {
+            ld_ks = 0;
+            ++ld_t;
+            const int t = ld_t < g.q ? ld_t : g.q - 1;
+            ld_ap = (const char*)ka->a[t];
+            ld_bp = (const char*)ka->b[t];
+        }
     };
 
-    if (kt_begin < kt_end) {
-        issue(kt_begin, 0);
-        commit(0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-    }
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        const int cur = (kt - kt_begin) & 1;
-        const bool more = kt + 1 < kt_end;
-        if (more) issue(kt + 1, cur ^ 1);
-        const char* sa = lds + cur * STAGE_BYTES;
-        const char* sb = sa + A_BYTES;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 af[FM], bfr[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) af[i] = ra.read(sa, i, kk);
-#pragma unroll
-            for (int j = 0; j < FN; ++j) bfr[j] = rb.read(sb, j, kk);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    bf16x8 af[2][FM], bfr[2][FN];
+    auto load_frags = [&](auto buf, int stage, auto kk) {
+        const char* sa = lds + stage * STAGE_BYTES;
+        static_for<FM>([&](auto i) { af[buf][i] = ra.read(sa, i, kk); });
+        static_for<FN>([&](auto j) { bfr[buf][j] = rb.read(sa + A_BYTES, j, kk); });
+    };
+    auto mfma_step = [&](auto buf) {
+        static_for<FM>([&](auto i) {
+            static_for<FN>([&](auto j) {
+                acc[i * FN + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    af[buf][i], bfr[buf][j], acc[i * FN + j], 0, 0, 0);
+            });
+        });
+    };
+    constexpr int DSR = (A_KC ? FM : 2 * FM) + (B_KC ? FN : 2 * FN);   // LDS reads per k16 step
+    // all k16 steps of a stage except the last: fetch the next step's fragments while
+    // the matrix pipe works on the current ones
+    auto body_steps = [&](int stage) {
+        static_for<KSTEPS - 1>([&](auto kk) {
+            load_frags(std::integral_constant<int, (kk + 1) & 1>{}, stage,
+                       std::integral_constant<int, kk + 1>{});
+            mfma_step(std::integral_constant<int, kk & 1>{});
+            static_for<DSR>([&](auto) {
+                SCHED_MFMA((FM * FN) / DSR > 0 ? (FM * FN) / DSR : 1);
+                SCHED_DSRD(1);
+            });
+        });
+    };
+    constexpr int LASTBUF = (KSTEPS - 1) & 1;
+
+    if constexpr (DIRECT) {
+        // Ring of NSTAGE LDS slots; tile r lives in slot r % NSTAGE.  All slots are
+        // requested up front; tile r+NSTAGE is requested into slot r % NSTAGE as soon
+        // as every wave has finished reading tile r, so NSTAGE-1 tiles are in flight
+        // or ready while one is being consumed.
+        static_for<NSTAGE>([&](auto s) {
+            if (s < nkt) { issue(s); advance(); }
+        });
+        // tile 0 must have landed; the later ones may still be in flight
+        if (nkt >= NSTAGE) wait_vmcnt<(NSTAGE - 1) * LOADS>();
+        else wait_vmcnt<0>();
+        lds_barrier();
+        if (nkt > 0) load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
+        int stage = 0;
+        int r = 0;
+        // steady state: a tile to request at every step
+        for (; r + NSTAGE < nkt; ++r) {
+            body_steps(stage);
+            const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of this slot are done
+            wait_vmcnt<(NSTAGE - 2) * LOADS>();                    // tile r+1 has landed
+            lds_barrier();
+            issue(stage);                                          // tile r+NSTAGE into the freed slot
+            load_frags(std::integral_constant<int, (LASTBUF ^ 1)>{}, next, std::integral_constant<int, 0>{});
+            mfma_step(std::integral_constant<int, LASTBUF>{});
+            static_for<FM * FN>([&](auto x) {
+                SCHED_MFMA(1);
+                if (x < LOADS) SCHED_VMEM(1);
+                if (x < DSR) SCHED_DSRD(1);
+            });
+            advance();
+            stage = next;
         }
-        if (more) commit(cur ^ 1);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        // drain: nothing left to request
+        for (; r < nkt; ++r) {
+            body_steps(stage);
+            const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            wait_vmcnt<0>();
+            lds_barrier();
+            if (r + 1 < nkt)
+                load_frags(std::integral_constant<int, (LASTBUF ^ 1)>{}, next, std::integral_constant<int, 0>{});
+            mfma_step(std::integral_constant<int, LASTBUF>{});
+            stage = next;
+        }
+    } else {
+        // register-staged double buffer with a zero-filled K tail
+        auto commit = [&](int stage) {
+            char* sa = lds + stage * STAGE_BYTES;
+            la.commit(sa, tid);
+            lb.commit(sa + A_BYTES, tid);
+        };
+        if (nkt > 0) {
+            issue(0);
+            advance();
+            commit(0);
+            __syncthreads();
+        }
+        for (int r = 0; r < nkt; ++r) {
+            const int cur = r & 1;
+            const bool more = r + 1 < nkt;
+            if (more) { issue(cur ^ 1); advance(); }
+            load_frags(std::integral_constant<int, 0>{}, cur, std::integral_constant<int, 0>{});
+            body_steps(cur);
+            mfma_step(std::integral_constant<int, LASTBUF>{});
+            if (more) commit(cur ^ 1);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue
@@ -383,28 +553,19 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
         // partial sums in accumulator order: [(z*nb + tile)][wave][frag][reg][lane]
         float* w = g.ws + ((size_t)blockIdx.z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
                    (size_t)wave * (FM * FN * 16 * 64) + lane;
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) w[((i * FN + j) * 16 + r) * 64] = acc[i][j][r];
+        static_for<FM * FN>([&](auto f) {
+            static_for<16>([&](auto r) { w[(f * 16 + r) * 64] = acc[f][r()]; });
+        });
         return;
     }
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
+    static_for<FN>([&](auto j) {
         const int col = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
-        if (col >= g.N) continue;
-        const float bv = g.bias ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col]) : 0.0f;
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < g.M) store_out(g, row, col, acc[i][j][r], bv);
-            }
-        }
-    }
+        const float bv = (g.bias && col < g.N) ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col]) : 0.0f;
+        static_for<FM>([&](auto i) {
+            const int frow0 = row0 + wm * (BM / 2) + i * 32 + 4 * (lane >> 5);
+            store_fragment(g, acc[i * FN + j], frow0, col, bv);
+        });
+    });
 }
 
 // Sums the K-split partials in ascending split order and applies the epilogue.
@@ -436,11 +597,11 @@ __global__ __launch_bounds__(NTHREADS) void tess_splitk_reduce_kernel(GemmArgs g
     }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC, bool DIRECT>
+template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, bool DIRECT>
 static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
-    constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
-    auto kern = tess_mfma_kernel<BM, BN, A_KC, B_KC, DIRECT>;
+    constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
+    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, A_KC, B_KC, DIRECT>;
     static bool attr_set = false;   // per instantiation; the attribute is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -461,21 +622,27 @@ static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
     return e;
 }
 
-template <int BM, int BN, bool DIRECT>
+template <int BM, int BN, int BK, int NSTAGE, bool DIRECT>
 static hipError_t launch_layout(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
-    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, true, false, DIRECT>(g, p, s);
-    if (g.a_kc && g.b_kc) return launch_one<BM, BN, true, true, DIRECT>(g, p, s);
-    if (!g.a_kc && !g.b_kc) return launch_one<BM, BN, false, false, DIRECT>(g, p, s);
+    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, true, false, DIRECT>(g, p, s);
+    if (g.a_kc && g.b_kc) return launch_one<BM, BN, BK, NSTAGE, true, true, DIRECT>(g, p, s);
+    if (!g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, false, false, DIRECT>(g, p, s);
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
-    if (p.bm == 256 && p.bn == 256)
-        return p.direct ? launch_layout<256, 256, true>(g, p, s) : launch_layout<256, 256, false>(g, p, s);
-    if (p.bm == 128 && p.bn == 128)
-        return p.direct ? launch_layout<128, 128, true>(g, p, s) : launch_layout<128, 128, false>(g, p, s);
+    if (p.bm == 256 && p.bn == 256) {
+        if (!p.direct) return hipErrorInvalidValue;
+        if (p.bk == 32) return launch_layout<256, 256, 32, 4, true>(g, p, s);
+        return launch_layout<256, 256, 64, 2, true>(g, p, s);
+    }
+    if (p.bm == 128 && p.bn == 128) {
+        if (!p.direct) return launch_layout<128, 128, 64, 2, false>(g, p, s);
+        if (p.bk == 32) return launch_layout<128, 128, 32, 4, true>(g, p, s);
+        return launch_layout<128, 128, 64, 4, true>(g, p, s);
+    }
     return hipErrorInvalidValue;
 }
 
