@@ -198,6 +198,21 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l of the wavefront
+// fills bytes [16*l, 16*l+16) behind the wave-uniform LDS address `lds_dst` (M0).
+// Written as inline assembly on purpose: the compiler then does not track these
+// loads, so it inserts no "wait for every outstanding load" before LDS reads of
+// other ring slots; completion is enforced by the explicit vmcnt waits in front of
+// the workgroup barriers instead.
+__device__ __forceinline__ void lds_dma16(const char* src, char* lds_dst)
+{
+    const uint32_t m0 = (uint32_t)(uintptr_t)(LDS_PTR(char))lds_dst;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(m0)
+                 : "memory", "m0");
+}
+
 template <int R, int BK, bool KC, bool DIRECT>
 struct TileLoader {
     static constexpr int CH = BK / 8;            // granules per row (KC)
@@ -236,20 +251,23 @@ struct TileLoader {
     // valid k from there (only used by the staged variant, for the zero-filled tail).
     // wave_u: wavefront index as a wave-uniform value (the LDS address of a direct
     // load is a scalar: base of the 64 granules that the wavefront's lanes fill).
+    template <typename IT>
+    __device__ __forceinline__ void issue_one(const char* base, char* lds_tile, int wave_u, int tid,
+                                              int krem, IT it)
+    {
+        if (DIRECT) {
+            const int wave_first = (it * NTHREADS + wave_u * 64) * 16;
+            lds_dma16(base + off[it], lds_tile + wave_first);
+        } else {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if ((int)kpos[it] < krem) v = *(const u32x4*)(base + off[it]);
+            stage[it] = v;
+        }
+    }
     __device__ __forceinline__ void issue(const char* base, char* lds_tile, int wave_u, int tid,
                                           int krem)
     {
-        static_for<ITERS>([&](auto it) {
-            if (DIRECT) {
-                const int wave_first = (it * NTHREADS + wave_u * 64) * 16;
-                __builtin_amdgcn_global_load_lds((const GLB_PTR(void))(base + off[it]),
-                                                 (LDS_PTR(void))(lds_tile + wave_first), 16, 0, 0);
-            } else {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if ((int)kpos[it] < krem) v = *(const u32x4*)(base + off[it]);
-                stage[it] = v;
-            }
-        });
+        static_for<ITERS>([&](auto it) { issue_one(base, lds_tile, wave_u, tid, krem, it); });
     }
     __device__ __forceinline__ void commit(char* lds_tile, int tid)
     {
@@ -362,11 +380,6 @@ __device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n,
     tn = in_band / rows;
 }
 
-// Scheduling hints: interleave LDS reads and global->LDS loads with the MFMAs of a
-// k16 step so that the matrix pipe does not wait for operands.
-#define SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
-#define SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
-#define SCHED_VMEM(n) __builtin_amdgcn_sched_group_barrier(0x020, n, 0)
 
 template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, bool DIRECT>
 __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
@@ -449,34 +462,42 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
     };
 
     bf16x8 af[2][FM], bfr[2][FN];
-    auto load_frags = [&](auto buf, int stage, auto kk) {
+    // Fragment u of a k16 step: the FN fragments of B first, then the FM of A (the
+    // first MFMAs of a step need af[0] and every bfr[j]).
+    auto load_frag = [&](auto buf, int stage, auto kk, auto u) {
         const char* sa = lds + stage * STAGE_BYTES;
-        static_for<FM>([&](auto i) { af[buf][i] = ra.read(sa, i, kk); });
-        static_for<FN>([&](auto j) { bfr[buf][j] = rb.read(sa + A_BYTES, j, kk); });
+        if constexpr (u < FN) bfr[buf][u] = rb.read(sa + A_BYTES, u, kk);
+        else af[buf][u - FN] = ra.read(sa, u - FN, kk);
     };
-    auto mfma_step = [&](auto buf) {
-        static_for<FM>([&](auto i) {
-            static_for<FN>([&](auto j) {
-                acc[i * FN + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    af[buf][i], bfr[buf][j], acc[i * FN + j], 0, 0, 0);
-            });
+    auto load_frags = [&](auto buf, int stage, auto kk) {
+        static_for<FM + FN>([&](auto u) { load_frag(buf, stage, kk, u); });
+    };
+    // One k16 step written out in issue order: MFMA x is followed by the side work
+    // side(x) (LDS reads of the next step, requests for a later tile), and a
+    // scheduling fence keeps the compiler from regrouping them, so the matrix pipe
+    // is fed while the reads and requests are in flight.
+    auto mfma_step = [&](auto buf, auto&& side) {
+        static_for<FM * FN>([&](auto x) {
+            constexpr int i = x / FN, j = x % FN;
+            acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[x], 0, 0, 0);
+            side(x);
+            __builtin_amdgcn_sched_barrier(0);
         });
     };
-    constexpr int DSR = (A_KC ? FM : 2 * FM) + (B_KC ? FN : 2 * FN);   // LDS reads per k16 step
-    // all k16 steps of a stage except the last: fetch the next step's fragments while
-    // the matrix pipe works on the current ones
+    // all k16 steps of a stage except the last: fetch the next step's fragments with
+    // the first MFMAs of the current one
     auto body_steps = [&](int stage) {
         static_for<KSTEPS - 1>([&](auto kk) {
-            load_frags(std::integral_constant<int, (kk + 1) & 1>{}, stage,
-                       std::integral_constant<int, kk + 1>{});
-            mfma_step(std::integral_constant<int, kk & 1>{});
-            static_for<DSR>([&](auto) {
-                SCHED_MFMA((FM * FN) / DSR > 0 ? (FM * FN) / DSR : 1);
-                SCHED_DSRD(1);
+            mfma_step(std::integral_constant<int, kk & 1>{}, [&](auto x) {
+                if constexpr (x < FM + FN)
+                    load_frag(std::integral_constant<int, (kk + 1) & 1>{}, stage,
+                              std::integral_constant<int, kk + 1>{}, x);
             });
         });
     };
     constexpr int LASTBUF = (KSTEPS - 1) & 1;
+    static_assert(FM + FN <= FM * FN, "one fragment read per MFMA slot");
+    auto no_side = [](auto) {};
 
     if constexpr (DIRECT) {
         // Ring of NSTAGE LDS slots; tile r lives in slot r % NSTAGE.  All slots are
@@ -493,6 +514,7 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
         if (nkt > 0) load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
         int stage = 0;
         int r = 0;
+        constexpr int LPS = (LOADS + FM * FN - 1) / (FM * FN);   // requests per MFMA slot
         // steady state: a tile to request at every step
         for (; r + NSTAGE < nkt; ++r) {
             body_steps(stage);
@@ -500,13 +522,19 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of this slot are done
             wait_vmcnt<(NSTAGE - 2) * LOADS>();                    // tile r+1 has landed
             lds_barrier();
-            issue(stage);                                          // tile r+NSTAGE into the freed slot
-            load_frags(std::integral_constant<int, (LASTBUF ^ 1)>{}, next, std::integral_constant<int, 0>{});
-            mfma_step(std::integral_constant<int, LASTBUF>{});
-            static_for<FM * FN>([&](auto x) {
-                SCHED_MFMA(1);
-                if (x < LOADS) SCHED_VMEM(1);
-                if (x < DSR) SCHED_DSRD(1);
+            // last k16 step of tile r, carrying the first fragments of tile r+1 and
+            // the requests for tile r+NSTAGE into the slot that was just freed
+            char* sa = lds + stage * STAGE_BYTES;
+            const int krem = g.Kp - ld_ks * BK;
+            mfma_step(std::integral_constant<int, LASTBUF>{}, [&](auto x) {
+                if constexpr (x < FM + FN)
+                    load_frag(std::integral_constant<int, (LASTBUF ^ 1)>{}, next,
+                              std::integral_constant<int, 0>{}, x);
+                static_for<LPS>([&](auto l) {
+                    constexpr int it = x * LPS + l;
+                    if constexpr (it < LA::ITERS) la.issue_one(ld_ap, sa, wave_u, tid, krem, std::integral_constant<int, it>{});
+                    else if constexpr (it < LOADS) lb.issue_one(ld_bp, sa + A_BYTES, wave_u, tid, krem, std::integral_constant<int, it - LA::ITERS>{});
+                });
             });
             advance();
             stage = next;
@@ -520,7 +548,7 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
             lds_barrier();
             if (r + 1 < nkt)
                 load_frags(std::integral_constant<int, (LASTBUF ^ 1)>{}, next, std::integral_constant<int, 0>{});
-            mfma_step(std::integral_constant<int, LASTBUF>{});
+            mfma_step(std::integral_constant<int, LASTBUF>{}, no_side);
             stage = next;
         }
     } else {
@@ -542,7 +570,7 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
             if (more) { issue(cur ^ 1); advance(); }
             load_frags(std::integral_constant<int, 0>{}, cur, std::integral_constant<int, 0>{});
             body_steps(cur);
-            mfma_step(std::integral_constant<int, LASTBUF>{});
+            mfma_step(std::integral_constant<int, LASTBUF>{}, no_side);
             if (more) commit(cur ^ 1);
             __syncthreads();
         }
