@@ -16,35 +16,50 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
     p.path = Path::Generic;
     p.bm = p.bn = 0;
     p.bk = 64;
+    p.waves = 4;
     p.splits = 1;
     p.direct = 0;
     p.ws_bytes = 0;
     if (!in_bf16) return p;
     p.path = Path::Mfma;
-    // 256 x 256 tiles when that still gives the 256 compute units enough work,
-    // otherwise 128 x 128
-    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
     const int64_t kt_total = (int64_t)q * ((Kp + BK_HOST - 1) / BK_HOST);
     p.direct = (Kp % BK_HOST == 0) ? 1 : 0;
-    // the register-staged loader (ragged K) only exists for the small tile
-    if (p.direct && M >= 256 && N >= 256 && t256 * (kt_total >= 8 ? 8 : 1) >= 192) {
-        p.bm = p.bn = 256;
-    } else {
-        p.bm = p.bn = 128;
+    // Tile and K-split are chosen with a small cost model in units of "one 64-deep
+    // stage of a 256 x 256 tile on one compute unit": a launch runs in rounds of 256
+    // workgroups, a workgroup costs its stages plus a fixed start/finish overhead, a
+    // 128 x 128 tile does a quarter of the work per stage at about half the
+    // efficiency (twice the panel traffic per flop), and every split adds one fp32
+    // partial tile to write and read back.
+    const double kOverheadStages = 6.0;
+    const double kPartialTileStages = 1.6;   // write + read of 256 KiB of partials
+    double best = 1e30;
+    const int cands[2] = {256, 128};
+    for (int ci = 0; ci < 2; ++ci) {
+        const int t = cands[ci];
+        // the register-staged loader (ragged K) only exists for the small tile
+        if (t == 256 && !(p.direct && M >= 256 && N >= 256)) continue;
+        const int64_t tiles = ((M + t - 1) / t) * ((N + t - 1) / t);
+        const double stage_cost = t == 256 ? 1.0 : 0.5;
+        const double partial_cost = t == 256 ? kPartialTileStages : kPartialTileStages / 4;
+        const int per_cu = t == 256 ? 1 : 2;              // resident workgroups per compute unit
+        for (int sp = 1; sp <= 16; ++sp) {
+            if (sp > 1 && kt_total / sp < 8) break;       // keep at least 8 stages per split
+            const int64_t wgs = tiles * sp;
+            const int64_t rounds = (wgs + 256 * per_cu - 1) / (256 * per_cu);
+            const double kt = (double)((kt_total + sp - 1) / sp);
+            double cost = rounds * per_cu * (kt * stage_cost + kOverheadStages * stage_cost);
+            if (sp > 1) cost += (double)sp * tiles * partial_cost / 256.0 + 2.0;
+            if (cost < best) { best = cost; p.bm = p.bn = t; p.splits = sp; }
+        }
     }
     const int64_t tiles = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
-    // split the K loop when one wave of tiles leaves most compute units idle
-    int splits = 1;
-    if (tiles < 160) {
-        splits = (int)((256 + tiles - 1) / tiles);
-        const int64_t max_by_k = kt_total / 8 > 0 ? kt_total / 8 : 1;   // >= 8 stages per split
-        if (splits > max_by_k) splits = (int)max_by_k;
-        if (splits > 32) splits = 32;
-        if (splits < 1) splits = 1;
-    }
-    p.splits = splits;
-    if (const char* e = getenv("TESS_BK")) p.bk = atoi(e) == 32 ? 32 : 64;   // tuning knob
-    if (splits > 1) p.ws_bytes = (size_t)splits * tiles * p.bm * p.bn * sizeof(float);
+    if (const char* e = getenv("TESS_BK")) p.bk = atoi(e) == 32 ? 32 : 64;   // tuning knobs
+    if (const char* e = getenv("TESS_WAVES")) p.waves = atoi(e) == 8 ? 8 : 4;
+    if (const char* e = getenv("TESS_SPLITS")) { const int v = atoi(e); if (v >= 1 && kt_total / v >= 1) p.splits = v; }
+    if (const char* e = getenv("TESS_TILE")) { const int v = atoi(e); if (v == 128 || (v == 256 && p.direct && M >= 256 && N >= 256)) p.bm = p.bn = v; }
+    const int64_t tiles2 = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
+    (void)tiles;
+    if (p.splits > 1) p.ws_bytes = (size_t)p.splits * tiles2 * p.bm * p.bn * sizeof(float);
     return p;
 }
 
@@ -103,6 +118,9 @@ static tess_status run(GemmArgs& g, void* workspace, size_t workspace_bytes, voi
         g.ws = static_cast<float*>(workspace);
     }
     g.splits = p.splits;
+#ifdef TESS_X_TIMING
+    g.ws = static_cast<float*>(workspace);
+#endif
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = (p.path == Path::Mfma) ? launch_mfma(g, p, s) : launch_generic(g, s);
     return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;

@@ -21,7 +21,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 #define GLB_PTR(T) __attribute__((address_space(1))) T*
 
-constexpr int NTHREADS = 256;   // 4 wavefronts, arranged 2 x 2 over the macro tile
 
 // ---------------------------------------------------------------------------
 // epilogue helpers
@@ -193,89 +192,121 @@ __device__ __forceinline__ void wait_vmcnt()
 // still in flight for later stages are not waited for.
 __device__ __forceinline__ void lds_barrier()
 {
+#ifdef TESS_X_NOBARRIER
+    return;
+#endif
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// 16 bytes per lane from global memory straight into LDS: lane l of the wavefront
-// fills bytes [16*l, 16*l+16) behind the wave-uniform LDS address `lds_dst` (M0).
-// Written as inline assembly on purpose: the compiler then does not track these
-// loads, so it inserts no "wait for every outstanding load" before LDS reads of
-// other ring slots; completion is enforced by the explicit vmcnt waits in front of
-// the workgroup barriers instead.
-__device__ __forceinline__ void lds_dma16(const char* src, char* lds_dst)
+// Granule index -> byte offset of that granule inside a panel at k0 = 0 (and, for
+// the staged loader, the k index inside the stage at which it starts).
+template <int R, int BK, bool KC>
+__device__ __forceinline__ uint32_t granule_offset(int G, int origin, int extent, int64_t ld,
+                                                   uint32_t* kpos)
 {
-    const uint32_t m0 = (uint32_t)(uintptr_t)(LDS_PTR(char))lds_dst;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(src), "s"(m0)
-                 : "memory", "m0");
+    constexpr int CH = BK / 8, RG = R / 8;
+    if (KC) {
+        const int r = G / CH, pc = G % CH;
+        const int c = pc ^ swz_kc<BK>(r);
+        int row = origin + r;
+        row = row < extent ? row : extent - 1;          // rows past the edge repeat the last row
+        if (kpos) *kpos = 8 * c;
+        return (uint32_t)(((int64_t)row * ld + 8 * c) * 2);
+    } else {
+        const int kr = G / RG, pg = G % RG;
+        const int gidx = pg ^ swz_mc(kr);
+        int col = origin + 8 * gidx;
+        col = col + 8 <= extent ? col : extent - 8;     // granules past the edge repeat the last one
+        if (kpos) *kpos = kr;
+        return (uint32_t)(((int64_t)kr * ld + col) * 2);
+    }
 }
 
-template <int R, int BK, bool KC, bool DIRECT>
-struct TileLoader {
-    static constexpr int CH = BK / 8;            // granules per row (KC)
-    static constexpr int NG = R * CH;            // granules per stage
-    static constexpr int ITERS = NG / NTHREADS;
-    static constexpr int RG = R / 8;             // granules per k-row (MC)
-    uint32_t off[ITERS];    // byte offset of this thread's granule inside a panel at k0 = 0
-    uint32_t kpos[DIRECT ? 1 : ITERS];   // k index (within the stage) that the granule starts at
-    u32x4 stage[DIRECT ? 1 : ITERS];
+// Direct global -> LDS loader.  One request is a 64-lane x 16-byte buffer load with
+// the LDS modifier: lane l's 16 bytes land at M0 + imm + 16*l, its source address is
+// descriptor base + per-lane offset + scalar offset + imm.  Wavefront w owns granules
+// [w*ITERS*64, (w+1)*ITERS*64) of the tile and fills them 64 at a time; groups of four
+// requests share one M0 value and differ in imm (1024 bytes apart in LDS), which the
+// per-lane offset compensates on the global side.  Written as inline assembly on
+// purpose: a wavefront can start only one such request per ~100 clocks, and the
+// scalar-base form with few M0 updates is the cheapest to issue; the compiler also
+// does not track these loads, so completion is enforced by the explicit vmcnt waits
+// in front of the workgroup barriers and no blanket wait precedes LDS reads.
+template <int R, int BK, bool KC, int NT>
+struct DmaLoader {
+    static constexpr int NG = R * (BK / 8);      // granules per stage
+    static constexpr int ITERS = NG / NT;        // requests per wavefront per stage
+    static constexpr uint32_t BIAS = 3072;       // keeps (offset - imm) non-negative
+    uint32_t off[ITERS];
+    u32x4 rsrc;                                  // buffer descriptor of the current panel
 
-    // origin: first row (KC) / first element along R (MC) of this block's tile;
-    // extent: total rows / elements of the operand along R; ld in elements.
+    __device__ __forceinline__ void init(int lane, int wave_u, int origin, int extent, int64_t ld)
+    {
+        static_for<ITERS>([&](auto it) {
+            const int G = (wave_u * ITERS + it) * 64 + lane;
+            off[it] = granule_offset<R, BK, KC>(G, origin, extent, ld, nullptr) + BIAS - (it % 4) * 1024;
+        });
+    }
+    __device__ __forceinline__ void set_panel(const void* panel)
+    {
+        const uint64_t base = (uint64_t)(uintptr_t)panel - BIAS;
+        rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+        rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);   // stride 0
+        rsrc[2] = 0xffffffffu;                   // no range clamp: every offset is in bounds
+        rsrc[3] = 0x00020000u;                   // raw 32-bit data format
+    }
+    // lds_stage: LDS byte address of this operand's tile in the destination stage;
+    // soff: byte advance of the stage along K inside the panel (wave-uniform).
+    template <typename IT>
+    __device__ __forceinline__ void request(IT it, uint32_t lds_stage, int wave_u, uint32_t soff) const
+    {
+#ifdef TESS_X_NOLOADS
+        if (lds_stage != 0xffffffffu) return;
+#endif
+        if constexpr (it % 4 == 0) {
+            const uint32_t m0 = lds_stage + (uint32_t)(wave_u * ITERS + it) * 1024u;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(m0) : "m0", "memory");
+        }
+#ifndef TESS_X_POLICY
+#define TESS_X_POLICY ""
+#endif
+        asm volatile("buffer_load_dwordx4 %0, %1, %2 offen offset:%3" TESS_X_POLICY " lds"
+                     :
+                     : "v"(off[it]), "s"(rsrc), "s"(soff), "n"((it % 4) * 1024)
+                     : "memory");
+    }
+};
+
+// Register-staged loader (global -> VGPR -> LDS) with a zero-filled K tail.
+template <int R, int BK, bool KC, int NT>
+struct StagedLoader {
+    static constexpr int NG = R * (BK / 8);
+    static constexpr int ITERS = NG / NT;
+    uint32_t off[ITERS];
+    uint32_t kpos[ITERS];
+    u32x4 stage[ITERS];
     __device__ __forceinline__ void init(int tid, int origin, int extent, int64_t ld)
     {
         static_for<ITERS>([&](auto it) {
-            const int G = it * NTHREADS + tid;
-            if (KC) {
-                const int r = G / CH, pc = G % CH;
-                const int c = pc ^ swz_kc<BK>(r);
-                int row = origin + r;
-                row = row < extent ? row : extent - 1;
-                off[it] = (uint32_t)(((int64_t)row * ld + 8 * c) * 2);
-                if (!DIRECT) kpos[it] = 8 * c;
-            } else {
-                const int kr = G / RG, pg = G % RG;
-                const int gidx = pg ^ swz_mc(kr);
-                int col = origin + 8 * gidx;
-                col = col + 8 <= extent ? col : extent - 8;
-                off[it] = (uint32_t)(((int64_t)kr * ld + col) * 2);
-                if (!DIRECT) kpos[it] = kr;
-            }
+            off[it] = granule_offset<R, BK, KC>(it * NT + tid, origin, extent, ld, &kpos[it]);
         });
     }
-
-    // base: panel pointer advanced to the stage's first k (uniform); krem: number of
-    // valid k from there (only used by the staged variant, for the zero-filled tail).
-    // wave_u: wavefront index as a wave-uniform value (the LDS address of a direct
-    // load is a scalar: base of the 64 granules that the wavefront's lanes fill).
-    template <typename IT>
-    __device__ __forceinline__ void issue_one(const char* base, char* lds_tile, int wave_u, int tid,
-                                              int krem, IT it)
+    // base: panel pointer advanced to the stage's first k; krem: valid k from there
+    __device__ __forceinline__ void fetch(const char* base, int krem)
     {
-        if (DIRECT) {
-            const int wave_first = (it * NTHREADS + wave_u * 64) * 16;
-            lds_dma16(base + off[it], lds_tile + wave_first);
-        } else {
+        static_for<ITERS>([&](auto it) {
             u32x4 v = {0u, 0u, 0u, 0u};
             if ((int)kpos[it] < krem) v = *(const u32x4*)(base + off[it]);
             stage[it] = v;
-        }
-    }
-    __device__ __forceinline__ void issue(const char* base, char* lds_tile, int wave_u, int tid,
-                                          int krem)
-    {
-        static_for<ITERS>([&](auto it) { issue_one(base, lds_tile, wave_u, tid, krem, it); });
+        });
     }
     __device__ __forceinline__ void commit(char* lds_tile, int tid)
     {
-        if (!DIRECT) {
-            static_for<ITERS>([&](auto it) {
-                *(u32x4*)(lds_tile + (it * NTHREADS + tid) * 16) = stage[it];
-            });
-        }
+        static_for<ITERS>([&](auto it) {
+            *(u32x4*)(lds_tile + (it * NT + tid) * 16) = stage[it];
+        });
     }
 };
 
@@ -381,10 +412,13 @@ __device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n,
 }
 
 
-template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, bool DIRECT>
-__global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
+// WGM x WGN wavefronts tile the BM x BN macro tile; each owns (BM/WGM) x (BN/WGN).
+template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT>
+__global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
 {
-    constexpr int FM = BM / 64, FN = BN / 64;          // fragments per wave tile
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;      // wave tile
+    constexpr int FM = WTM / 32, FN = WTN / 32;        // 32x32 fragments per wave tile
     constexpr int KSTEPS = BK / 16;
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -393,7 +427,7 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int nb = tiles_m * tiles_n;
     int tm, tn;
@@ -412,17 +446,15 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
     }
     const int nkt = kt_end - kt_begin;
 
-    typedef TileLoader<BM, BK, A_KC, DIRECT> LA;
-    typedef TileLoader<BN, BK, B_KC, DIRECT> LB;
-    constexpr int LOADS = LA::ITERS + LB::ITERS;       // global loads per thread per stage
-    LA la;
-    LB lb;
-    la.init(tid, row0, g.M, g.lda);
-    lb.init(tid, col0, g.N, g.ldb);
+    typedef DmaLoader<BM, BK, A_KC, NT> LA;
+    typedef DmaLoader<BN, BK, B_KC, NT> LB;
+    typedef StagedLoader<BM, BK, A_KC, NT> SA;
+    typedef StagedLoader<BN, BK, B_KC, NT> SB;
+    constexpr int LOADS = LA::ITERS + LB::ITERS;       // requests per wavefront per stage
     FragReader<BM, BK, A_KC> ra;
     FragReader<BN, BK, B_KC> rb;
-    ra.init(lane, wm * (BM / 2));
-    rb.init(lane, wn * (BN / 2));
+    ra.init(lane, wm * WTM);
+    rb.init(lane, wn * WTN);
 
     floatx16 acc[FM * FN];
     static_for<FM * FN>([&](auto f) {
@@ -430,41 +462,25 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
     });
 
     // byte advance of one stage along K for each operand
-    const int64_t a_kstep = A_KC ? (int64_t)BK * 2 : (int64_t)BK * g.lda * 2;
-    const int64_t b_kstep = B_KC ? (int64_t)BK * 2 : (int64_t)BK * g.ldb * 2;
+    const uint32_t a_kstep = A_KC ? (uint32_t)BK * 2 : (uint32_t)(BK * g.lda * 2);
+    const uint32_t b_kstep = B_KC ? (uint32_t)BK * 2 : (uint32_t)(BK * g.ldb * 2);
 
     // Panel pointers are fetched from the kernel-argument segment (constant address
     // space, scalar loads) with the uniform step index; indexing the by-value copy
     // of the argument struct dynamically would move it to scratch memory.
     typedef __attribute__((address_space(4))) const GemmArgs* KernArgs;
     const KernArgs ka = (KernArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    // (panel, stage-in-panel) of the next stage to fetch and its operand pointers,
-    // advanced incrementally; the pointers are re-read only when the panel changes
+    // (panel, stage-in-panel) of the next stage to fetch, advanced incrementally
     int ld_t = kt_begin / kt_per_panel, ld_ks = kt_begin - ld_t * kt_per_panel;
-    const char* ld_ap = (const char*)ka->a[ld_t < g.q ? ld_t : 0] + ld_ks * a_kstep;
-    const char* ld_bp = (const char*)ka->b[ld_t < g.q ? ld_t : 0] + ld_ks * b_kstep;
-    auto issue = [&](int stage) {
-        char* sa = lds + stage * STAGE_BYTES;
-        const int krem = g.Kp - ld_ks * BK;
-        la.issue(ld_ap, sa, wave_u, tid, krem);
-        lb.issue(ld_bp, sa + A_BYTES, wave_u, tid, krem);
-    };
-    auto advance = [&]() {
-        ld_ap += a_kstep;
-        ld_bp += b_kstep;
-        if (++ld_ks == kt_per_panel) {
-            ld_ks = 0;
-            ++ld_t;
-            const int t = ld_t < g.q ? ld_t : g.q - 1;
-            ld_ap = (const char*)ka->a[t];
-            ld_bp = (const char*)ka->b[t];
-        }
-    };
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
 
     bf16x8 af[2][FM], bfr[2][FN];
     // Fragment u of a k16 step: the FN fragments of B first, then the FM of A (the
     // first MFMAs of a step need af[0] and every bfr[j]).
     auto load_frag = [&](auto buf, int stage, auto kk, auto u) {
+#ifdef TESS_X_NOREADS
+        if (stage >= 0) return;
+#endif
         const char* sa = lds + stage * STAGE_BYTES;
         if constexpr (u < FN) bfr[buf][u] = rb.read(sa + A_BYTES, u, kk);
         else af[buf][u - FN] = ra.read(sa, u - FN, kk);
@@ -479,98 +495,183 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
     auto mfma_step = [&](auto buf, auto&& side) {
         static_for<FM * FN>([&](auto x) {
             constexpr int i = x / FN, j = x % FN;
+#ifdef TESS_X_NOMFMA
+            if (x == 0) acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[x], 0, 0, 0);
+#else
             acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[x], 0, 0, 0);
+#endif
             side(x);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    // all k16 steps of a stage except the last: fetch the next step's fragments with
-    // the first MFMAs of the current one
-    auto body_steps = [&](int stage) {
+    constexpr int LASTBUF = (KSTEPS - 1) & 1;
+    constexpr int NSLOT = KSTEPS * FM * FN;            // MFMA slots per tile
+    static_assert(FM + FN <= FM * FN, "one fragment read per MFMA slot");
+    // request number `it` of a tile is attached to MFMA slot it*NSLOT/LOADS of the
+    // period that follows the barrier which frees the destination slot, so the
+    // requests trickle out at the rate the texture path can take them
+    LA la;
+    LB lb;
+    uint32_t rq_stage = 0;          // LDS address of the stage being filled
+    uint32_t rq_asoff = 0, rq_bsoff = 0;   // K advance of that tile inside its panels
+    auto set_panels = [&]() {
+        const int t = ld_t < g.q ? ld_t : g.q - 1;
+        la.set_panel(ka->a[t]);
+        lb.set_panel(ka->b[t]);
+    };
+    auto advance = [&]() {
+        if (++ld_ks == kt_per_panel) {
+            ld_ks = 0;
+            ++ld_t;
+            set_panels();
+        }
+    };
+    auto request = [&](auto it) {
+        if constexpr (it < LA::ITERS) la.request(it, rq_stage, wave_u, rq_asoff);
+        else lb.request(std::integral_constant<int, it - LA::ITERS>{}, rq_stage + A_BYTES, wave_u, rq_bsoff);
+    };
+    auto aim = [&](int stage) {     // point the requests at `stage` and the next tile
+        rq_stage = lds_base + stage * STAGE_BYTES;
+        rq_asoff = ld_ks * a_kstep;
+        rq_bsoff = ld_ks * b_kstep;
+    };
+    // with three or more stages a tile has more than a period to land and its requests
+    // are spread over the whole period; with two stages they go out in the first half
+    constexpr int RQ_SPAN = NSTAGE >= 3 ? NSLOT : NSLOT / 2;
+    constexpr int STRIDE = RQ_SPAN / LOADS;
+    static_assert(RQ_SPAN % LOADS == 0 && STRIDE >= 1, "requests spaced evenly over the MFMA slots");
+    auto request_at = [&](auto slot) {
+        if constexpr (slot % STRIDE == 0 && slot / STRIDE < LOADS)
+            request(std::integral_constant<int, slot / STRIDE>{});
+    };
+    // The k16 steps 0 .. KSTEPS-2 of the tile in `stage`: each fetches the next step's
+    // fragments with its first MFMAs.  REQ: also carry requests (slots FM*FN ..).
+    auto body_steps = [&](int stage, auto req) {
         static_for<KSTEPS - 1>([&](auto kk) {
             mfma_step(std::integral_constant<int, kk & 1>{}, [&](auto x) {
                 if constexpr (x < FM + FN)
                     load_frag(std::integral_constant<int, (kk + 1) & 1>{}, stage,
                               std::integral_constant<int, kk + 1>{}, x);
+                if constexpr (req) request_at(std::integral_constant<int, (kk + 1) * FM * FN + x>{});
             });
         });
     };
-    constexpr int LASTBUF = (KSTEPS - 1) & 1;
-    static_assert(FM + FN <= FM * FN, "one fragment read per MFMA slot");
-    auto no_side = [](auto) {};
+    // The last k16 step of a tile, carrying the first fragments of the tile in `next`
+    // (FETCH) and the first requests (REQ, slots 0 .. FM*FN-1).
+    auto last_step = [&](int next, auto fetch, auto req) {
+        mfma_step(std::integral_constant<int, LASTBUF>{}, [&](auto x) {
+            if constexpr (fetch && x < FM + FN)
+                load_frag(std::integral_constant<int, (LASTBUF ^ 1)>{}, next,
+                          std::integral_constant<int, 0>{}, x);
+            if constexpr (req) request_at(std::integral_constant<int, x>{});
+        });
+    };
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
 
     if constexpr (DIRECT) {
         // Ring of NSTAGE LDS slots; tile r lives in slot r % NSTAGE.  All slots are
-        // requested up front; tile r+NSTAGE is requested into slot r % NSTAGE as soon
-        // as every wave has finished reading tile r, so NSTAGE-1 tiles are in flight
-        // or ready while one is being consumed.
+        // requested up front.  Barrier r (every wave has read tile r, tile r+1 has
+        // landed) frees slot r % NSTAGE; tile r+NSTAGE is then requested into it,
+        // spread over the MFMAs up to barrier r+1.  It is needed at barrier
+        // r+NSTAGE-1, so its requests have NSTAGE-2 tile periods to complete.
+        la.init(lane, wave_u, row0, g.M, g.lda);
+        lb.init(lane, wave_u, col0, g.N, g.ldb);
+        set_panels();
         static_for<NSTAGE>([&](auto s) {
-            if (s < nkt) { issue(s); advance(); }
+            if (s < nkt) {
+                aim(s);
+                static_for<LOADS>([&](auto it) { request(it); });
+                advance();
+            }
         });
         // tile 0 must have landed; the later ones may still be in flight
         if (nkt >= NSTAGE) wait_vmcnt<(NSTAGE - 1) * LOADS>();
         else wait_vmcnt<0>();
         lds_barrier();
-        if (nkt > 0) load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
         int stage = 0;
+        if (nkt > 0) {
+            load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
+            body_steps(0, no);
+        }
         int r = 0;
-        constexpr int LPS = (LOADS + FM * FN - 1) / (FM * FN);   // requests per MFMA slot
-        // steady state: a tile to request at every step
+        // steady state: tile r+NSTAGE exists and is requested during period r
         for (; r + NSTAGE < nkt; ++r) {
-            body_steps(stage);
             const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of this slot are done
+#ifdef TESS_X_TIMING
+            const long long t0 = clock64();
+#endif
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of tile r are done
+#ifdef TESS_X_TIMING
+            const long long t1 = clock64();
+#endif
             wait_vmcnt<(NSTAGE - 2) * LOADS>();                    // tile r+1 has landed
-            lds_barrier();
-            // last k16 step of tile r, carrying the first fragments of tile r+1 and
-            // the requests for tile r+NSTAGE into the slot that was just freed
-            char* sa = lds + stage * STAGE_BYTES;
-            const int krem = g.Kp - ld_ks * BK;
-            mfma_step(std::integral_constant<int, LASTBUF>{}, [&](auto x) {
-                if constexpr (x < FM + FN)
-                    load_frag(std::integral_constant<int, (LASTBUF ^ 1)>{}, next,
-                              std::integral_constant<int, 0>{}, x);
-                static_for<LPS>([&](auto l) {
-                    constexpr int it = x * LPS + l;
-                    if constexpr (it < LA::ITERS) la.issue_one(ld_ap, sa, wave_u, tid, krem, std::integral_constant<int, it>{});
-                    else if constexpr (it < LOADS) lb.issue_one(ld_bp, sa + A_BYTES, wave_u, tid, krem, std::integral_constant<int, it - LA::ITERS>{});
-                });
-            });
+#ifdef TESS_X_TIMING
+            const long long t2 = clock64();
+#endif
+            lds_barrier();                                         // barrier r
+#ifdef TESS_X_TIMING
+            const long long t3 = clock64();
+#endif
+            aim(stage);
+            last_step(next, yes, yes);
+#ifdef TESS_X_TIMING
+            const long long t4 = clock64();
+#endif
+            body_steps(next, yes);
             advance();
             stage = next;
+#ifdef TESS_X_TIMING
+            if (blockIdx.x == 37 && lane == 0 && r >= 16 && r < 16 + 64 && g.ws) {
+                long long* o = (long long*)g.ws + ((r - 16) * 8 + wave) * 8;
+                o[0] = t0; o[1] = t1; o[2] = t2; o[3] = t3; o[4] = t4; o[5] = clock64();
+            }
+#endif
         }
         // drain: nothing left to request
         for (; r < nkt; ++r) {
-            body_steps(stage);
             const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             wait_vmcnt<0>();
             lds_barrier();
-            if (r + 1 < nkt)
-                load_frags(std::integral_constant<int, (LASTBUF ^ 1)>{}, next, std::integral_constant<int, 0>{});
-            mfma_step(std::integral_constant<int, LASTBUF>{}, no_side);
+            if (r + 1 < nkt) {
+                last_step(next, yes, no);
+                body_steps(next, no);
+            } else {
+                last_step(next, no, no);
+            }
             stage = next;
         }
     } else {
         // register-staged double buffer with a zero-filled K tail
+        SA sa_;
+        SB sb_;
+        sa_.init(tid, row0, g.M, g.lda);
+        sb_.init(tid, col0, g.N, g.ldb);
+        auto fetch = [&]() {
+            const int t = ld_t < g.q ? ld_t : g.q - 1;
+            const int krem = g.Kp - ld_ks * BK;
+            sa_.fetch((const char*)ka->a[t] + (size_t)ld_ks * a_kstep, krem);
+            sb_.fetch((const char*)ka->b[t] + (size_t)ld_ks * b_kstep, krem);
+            if (++ld_ks == kt_per_panel) { ld_ks = 0; ++ld_t; }
+        };
         auto commit = [&](int stage) {
-            char* sa = lds + stage * STAGE_BYTES;
-            la.commit(sa, tid);
-            lb.commit(sa + A_BYTES, tid);
+            char* st = lds + stage * STAGE_BYTES;
+            sa_.commit(st, tid);
+            sb_.commit(st + A_BYTES, tid);
         };
         if (nkt > 0) {
-            issue(0);
-            advance();
+            fetch();
             commit(0);
             __syncthreads();
         }
         for (int r = 0; r < nkt; ++r) {
             const int cur = r & 1;
             const bool more = r + 1 < nkt;
-            if (more) { issue(cur ^ 1); advance(); }
+            if (more) fetch();
             load_frags(std::integral_constant<int, 0>{}, cur, std::integral_constant<int, 0>{});
-            body_steps(cur);
-            mfma_step(std::integral_constant<int, LASTBUF>{}, no_side);
+            body_steps(cur, no);
+            last_step(cur, no, no);
             if (more) commit(cur ^ 1);
             __syncthreads();
         }
@@ -587,49 +688,63 @@ __global__ __launch_bounds__(NTHREADS) void tess_mfma_kernel(GemmArgs g)
         return;
     }
     static_for<FN>([&](auto j) {
-        const int col = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
+        const int col = col0 + wn * WTN + j * 32 + (lane & 31);
         const float bv = (g.bias && col < g.N) ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col]) : 0.0f;
         static_for<FM>([&](auto i) {
-            const int frow0 = row0 + wm * (BM / 2) + i * 32 + 4 * (lane >> 5);
+            const int frow0 = row0 + wm * WTM + i * 32 + 4 * (lane >> 5);
             store_fragment(g, acc[i * FN + j], frow0, col, bv);
         });
     });
 }
 
 // Sums the K-split partials in ascending split order and applies the epilogue.
-template <int BM, int BN>
-__global__ __launch_bounds__(NTHREADS) void tess_splitk_reduce_kernel(GemmArgs g)
+// One thread per four consecutive accumulator lanes (same row, four adjacent
+// columns): 16-byte reads of every split's partial, all splits in flight at once.
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256) void tess_splitk_reduce_kernel(GemmArgs g)
 {
-    constexpr int FM = BM / 64, FN = BN / 64;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int FM = WTM / 32, FN = WTN / 32;
+    constexpr int PER_TILE = BM * BN / 4;
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
     const int tiles_n = (g.N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
-    const int nb = tiles_m * tiles_n;
-    const int tile = blockIdx.x;
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
-    const int row0 = tm * BM, col0 = tn * BN;
-    const float* w0 = g.ws + (size_t)tile * (BM * BN) + (size_t)wave * (FM * FN * 16 * 64) + lane;
-    for (int j = 0; j < FN; ++j) {
-        const int col = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
-        const float bv = (g.bias && col < g.N) ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col]) : 0.0f;
-        for (int i = 0; i < FM; ++i) {
-#pragma unroll 4
-            for (int r = 0; r < 16; ++r) {
-                float sum = 0.0f;
-                for (int z = 0; z < g.splits; ++z)
-                    sum += w0[(size_t)z * nb * (BM * BN) + ((i * FN + j) * 16 + r) * 64];
-                const int row = row0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < g.M && col < g.N) store_out(g, row, col, sum, bv);
-            }
+    const int64_t nb = (int64_t)tiles_m * tiles_n;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t tile = gid / PER_TILE;
+    if (tile >= nb) return;
+    const int idx = (int)(gid % PER_TILE) * 4;           // position in accumulator order
+    const int lane = idx & 63, r = (idx >> 6) & 15, f = (idx >> 10) % (FM * FN);
+    const int wave = idx / (1024 * FM * FN);
+    const int wm = wave / WGN, wn = wave % WGN, i = f / FN, j = f % FN;
+    const int tm = (int)(tile / tiles_n), tn = (int)(tile % tiles_n);
+    const int row = tm * BM + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    const int col = tn * BN + wn * WTN + j * 32 + (lane & 31);
+    if (row >= g.M || col >= g.N) return;
+    const floatx4* w = (const floatx4*)(g.ws + (size_t)tile * (BM * BN) + idx);
+    const size_t zstride = (size_t)nb * (BM * BN) / 4;
+    floatx4 sum = {0.f, 0.f, 0.f, 0.f};
+    int z = 0;
+    for (; z + 4 <= g.splits; z += 4) {
+        const floatx4 v0 = w[(size_t)z * zstride], v1 = w[(size_t)(z + 1) * zstride];
+        const floatx4 v2 = w[(size_t)(z + 2) * zstride], v3 = w[(size_t)(z + 3) * zstride];
+        sum += v0; sum += v1; sum += v2; sum += v3;
+    }
+    for (; z < g.splits; ++z) sum += w[(size_t)z * zstride];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (col + e < g.N) {
+            const float bv = g.bias ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col + e]) : 0.0f;
+            store_out(g, row, col + e, sum[e], bv);
         }
     }
 }
 
-template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, bool DIRECT>
+template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT>
 static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
-    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, A_KC, B_KC, DIRECT>;
+    constexpr int NT = 64 * WGM * WGN;
+    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT>;
     static bool attr_set = false;   // per instantiation; the attribute is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -640,22 +755,24 @@ static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
     const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     GemmArgs a = g;
     a.splits = p.splits;
-    hipLaunchKernelGGL(kern, dim3(tiles, 1, p.splits), dim3(NTHREADS), lds_bytes, s, a);
+    hipLaunchKernelGGL(kern, dim3(tiles, 1, p.splits), dim3(NT), lds_bytes, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.splits > 1) {
-        hipLaunchKernelGGL((tess_splitk_reduce_kernel<BM, BN>), dim3(tiles), dim3(NTHREADS), 0, s, a);
+        const int64_t groups = (int64_t)tiles * (BM * BN / 4);
+        hipLaunchKernelGGL((tess_splitk_reduce_kernel<BM, BN, WGM, WGN>), dim3((unsigned)((groups + 255) / 256)),
+                           dim3(256), 0, s, a);
         e = hipGetLastError();
     }
     return e;
 }
 
-template <int BM, int BN, int BK, int NSTAGE, bool DIRECT>
+template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool DIRECT>
 static hipError_t launch_layout(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
-    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, true, false, DIRECT>(g, p, s);
-    if (g.a_kc && g.b_kc) return launch_one<BM, BN, BK, NSTAGE, true, true, DIRECT>(g, p, s);
-    if (!g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, false, false, DIRECT>(g, p, s);
+    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, false, DIRECT>(g, p, s);
+    if (g.a_kc && g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, true, DIRECT>(g, p, s);
+    if (!g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT>(g, p, s);
     return hipErrorInvalidValue;
 }
 
@@ -663,13 +780,17 @@ hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     if (p.bm == 256 && p.bn == 256) {
         if (!p.direct) return hipErrorInvalidValue;
-        if (p.bk == 32) return launch_layout<256, 256, 32, 4, true>(g, p, s);
-        return launch_layout<256, 256, 64, 2, true>(g, p, s);
+        if (p.bk == 32) {
+            if (p.waves == 4) return launch_layout<256, 256, 32, 4, 2, 2, true>(g, p, s);
+            return launch_layout<256, 256, 32, 4, 2, 4, true>(g, p, s);
+        }
+        if (p.waves == 4) return launch_layout<256, 256, 64, 2, 2, 2, true>(g, p, s);
+        return launch_layout<256, 256, 64, 2, 2, 4, true>(g, p, s);
     }
     if (p.bm == 128 && p.bn == 128) {
-        if (!p.direct) return launch_layout<128, 128, 64, 2, false>(g, p, s);
-        if (p.bk == 32) return launch_layout<128, 128, 32, 4, true>(g, p, s);
-        return launch_layout<128, 128, 64, 4, true>(g, p, s);
+        if (!p.direct) return launch_layout<128, 128, 64, 2, 2, 2, false>(g, p, s);
+        if (p.bk == 32) return launch_layout<128, 128, 32, 4, 2, 2, true>(g, p, s);
+        return launch_layout<128, 128, 64, 3, 2, 2, true>(g, p, s);
     }
     return hipErrorInvalidValue;
 }
