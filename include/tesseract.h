@@ -124,6 +124,14 @@ tess_status tess_linear_bwd_dw(const tess_desc* desc,
  * descriptor on the current device (0 when none).  Pure host arithmetic. */
 size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
 
+/* Launch shape that the call `op` would use for this descriptor when operands are
+ * 16-byte aligned: output macro tile and number of K splits (1 = the whole q-step
+ * sum stays in one workgroup's registers; > 1 = partial sums go through the
+ * workspace and a reduction kernel applies the epilogue).  tile 0 x 0 means the
+ * plain fp32 kernel.  Pure host arithmetic. */
+tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int32_t* tile_n,
+                             int32_t* k_splits);
+
 /* Validates a descriptor alone (grid rules and divisibility). */
 tess_status tess_desc_check(const tess_desc* desc);
 

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
 
 EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
-           "tess_linear_workspace_bytes", "tess_desc_check", "tess_block_shape",
+           "tess_linear_workspace_bytes", "tess_linear_plan", "tess_desc_check", "tess_block_shape",
            "tess_status_string", "tess_version"]
 
 
@@ -59,6 +59,9 @@ def lib():
         L.tess_linear_bwd_dw.argtypes = [dp, pp, i64, pp, i64, vp, i64, cint, vp, sz, vp]
         L.tess_linear_workspace_bytes.restype = sz
         L.tess_linear_workspace_bytes.argtypes = [dp, cint]
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        L.tess_linear_plan.restype = cint
+        L.tess_linear_plan.argtypes = [dp, cint, i32p, i32p, i32p]
         L.tess_desc_check.restype = cint
         L.tess_desc_check.argtypes = [dp]
         L.tess_block_shape.restype = cint
@@ -107,6 +110,16 @@ def block_shape(desc):
 
 def workspace_bytes(desc, op):
     return lib().tess_linear_workspace_bytes(ctypes.byref(desc), op)
+
+
+def plan(desc, op):
+    """(tile_m, tile_n, k_splits) of the launch the library would choose."""
+    tm, tn, ks = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    st = lib().tess_linear_plan(ctypes.byref(desc), op, ctypes.byref(tm), ctypes.byref(tn),
+                                ctypes.byref(ks))
+    if st:
+        raise TessError(st, "tess_linear_plan")
+    return tm.value, tn.value, ks.value
 
 
 def _panel_array(panels, rows, cols, what):

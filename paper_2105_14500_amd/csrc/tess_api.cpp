@@ -159,6 +159,26 @@ size_t tess_linear_workspace_bytes(const tess_desc* desc, int op)
     }
 }
 
+tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int32_t* tile_n,
+                             int32_t* k_splits)
+{
+    tess_status st = check_desc(desc);
+    if (st != TESS_OK) return st;
+    if (!tile_m || !tile_n || !k_splits) return TESS_ERR_NULL;
+    const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
+                  n = desc->c / desc->q;
+    const bool bf = desc->in_dtype == TESS_BF16;
+    Plan p;
+    switch (op) {
+        case TESS_OP_FWD: p = shape_plan(m, n, kb, desc->q, bf); break;
+        case TESS_OP_BWD_DX: p = shape_plan(m, kb, n, desc->q, bf); break;
+        case TESS_OP_BWD_DW: p = shape_plan(kb, n, m, desc->q, bf); break;
+        default: return TESS_ERR_UNSUPPORTED;
+    }
+    *tile_m = p.bm; *tile_n = p.bn; *k_splits = p.splits;
+    return TESS_OK;
+}
+
 tess_status tess_linear_fwd(const tess_desc* desc, const void* const* a_panels, int64_t lda,
                             const void* const* b_panels, int64_t ldb, const void* bias, int act,
                             void* c_out, int64_t ldc, void* preact_out, void* workspace,
