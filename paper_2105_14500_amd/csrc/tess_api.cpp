@@ -118,7 +118,7 @@ static tess_status run(GemmArgs& g, void* workspace, size_t workspace_bytes, voi
         g.ws = static_cast<float*>(workspace);
     }
     g.splits = p.splits;
-#ifdef TESS_X_TIMING
+#if defined(TESS_X_TIMING) || defined(TESS_X_TIMING2)
     g.ws = static_cast<float*>(workspace);
 #endif
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -185,6 +185,9 @@ __device__ __forceinline__ void static_for(F&& f)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
+#ifdef TESS_X_NOWAIT
+    if (N >= 0) return;
+#endif
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
@@ -240,7 +243,6 @@ struct DmaLoader {
     static constexpr int ITERS = NG / NT;        // requests per wavefront per stage
     static constexpr uint32_t BIAS = 3072;       // keeps (offset - imm) non-negative
     uint32_t off[ITERS];
-    u32x4 rsrc;                                  // buffer descriptor of the current panel
 
     __device__ __forceinline__ void init(int lane, int wave_u, int origin, int extent, int64_t ld)
     {
@@ -249,18 +251,22 @@ struct DmaLoader {
             off[it] = granule_offset<R, BK, KC>(G, origin, extent, ld, nullptr) + BIAS - (it % 4) * 1024;
         });
     }
-    __device__ __forceinline__ void set_panel(const void* panel)
+    // buffer descriptor of a panel (kept by the caller in scalar registers)
+    static __device__ __forceinline__ u32x4 descriptor(const void* panel)
     {
         const uint64_t base = (uint64_t)(uintptr_t)panel - BIAS;
+        u32x4 rsrc;
         rsrc[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
         rsrc[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);   // stride 0
         rsrc[2] = 0xffffffffu;                   // no range clamp: every offset is in bounds
         rsrc[3] = 0x00020000u;                   // raw 32-bit data format
+        return rsrc;
     }
     // lds_stage: LDS byte address of this operand's tile in the destination stage;
     // soff: byte advance of the stage along K inside the panel (wave-uniform).
     template <typename IT>
-    __device__ __forceinline__ void request(IT it, uint32_t lds_stage, int wave_u, uint32_t soff) const
+    __device__ __forceinline__ void request(IT it, const u32x4& rsrc, uint32_t lds_stage, int wave_u,
+                                            uint32_t soff) const
     {
 #ifdef TESS_X_NOLOADS
         if (lds_stage != 0xffffffffu) return;
@@ -272,9 +278,15 @@ struct DmaLoader {
 #ifndef TESS_X_POLICY
 #define TESS_X_POLICY ""
 #endif
+        // the descriptor must sit in scalar registers whatever the optimizer did to it
+        u32x4 d;
+        d[0] = __builtin_amdgcn_readfirstlane(rsrc[0]);
+        d[1] = __builtin_amdgcn_readfirstlane(rsrc[1]);
+        d[2] = __builtin_amdgcn_readfirstlane(rsrc[2]);
+        d[3] = __builtin_amdgcn_readfirstlane(rsrc[3]);
         asm volatile("buffer_load_dwordx4 %0, %1, %2 offen offset:%3" TESS_X_POLICY " lds"
                      :
-                     : "v"(off[it]), "s"(rsrc), "s"(soff), "n"((it % 4) * 1024)
+                     : "v"(off[it]), "s"(d), "s"(soff), "n"((it % 4) * 1024)
                      : "memory");
     }
 };
@@ -350,46 +362,69 @@ struct FragReader {
     }
 };
 
-// Stores one 32x32 accumulator fragment.  Accumulator layout: lane l, register r ->
-//   row = 8*(r/4) + 4*(l/32) + r%4,  col = l%32.
-// frow0: first row of the fragment + 4*(l/32); col: this lane's column.
-__device__ __forceinline__ void store_fragment(const GemmArgs& g, const floatx16& v, int frow0,
-                                               int col, float bias_v)
+// Epilogue for four adjacent columns of one output row: bias, optional copy of the
+// pre-activation, activation, then store or accumulate in the output dtype.  `vec`:
+// rows are 16-byte aligned, so the four values go out as one store.  The mode flags
+// are template parameters so that the drain loop of the common cases is a handful of
+// instructions; MODE_GENERIC reads them from the arguments instead.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// four fp32 -> four bf16 (round to nearest even, the hardware conversion of gfx950)
+__device__ __forceinline__ u32x2 pack_bf16x4(floatx4 v)
 {
-    if (col >= g.N) return;
-    float z[16];
-    static_for<16>([&](auto r) { z[r] = v[r()] + bias_v; });
-    if (g.preact) {
-        static_for<16>([&](auto r) {
-            const int row = frow0 + 8 * (r / 4) + (r % 4);
-            if (row < g.M) {
-                const int64_t o = (int64_t)row * g.ldo + col;
-                if (g.out_f32) ((float*)g.preact)[o] = z[r];
-                else ((uint16_t*)g.preact)[o] = f32_to_bf16_bits(z[r]);
-            }
-        });
-    }
-    if (g.act == TESS_ACT_GELU_ERF) static_for<16>([&](auto r) { z[r] = gelu_erf_f(z[r]); });
-    else if (g.act == TESS_ACT_GELU_TANH) static_for<16>([&](auto r) { z[r] = gelu_tanh_f(z[r]); });
-    if (g.out_f32) {
-        float* out = (float*)g.out;
-        if (g.accumulate) {
-            static_for<16>([&](auto r) {
-                const int row = frow0 + 8 * (r / 4) + (r % 4);
-                if (row < g.M) out[(int64_t)row * g.ldo + col] += z[r];
-            });
+    const floatx2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
+    u32x2 w;
+    w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+    w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+    return w;
+}
+
+enum : int { MODE_BF16 = 0, MODE_BF16_GELU = 1, MODE_F32 = 2, MODE_F32_ACC = 3, MODE_GENERIC = 4 };
+
+template <int MODE>
+__device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, floatx4 v, floatx4 bias,
+                                      bool vec)
+{
+    const bool out_f32 = MODE == MODE_GENERIC ? (g.out_f32 != 0) : (MODE == MODE_F32 || MODE == MODE_F32_ACC);
+    const bool accumulate = MODE == MODE_GENERIC ? (g.accumulate != 0) : (MODE == MODE_F32_ACC);
+    const bool preact = MODE == MODE_GENERIC ? (g.preact != nullptr) : false;
+    const int act = MODE == MODE_GENERIC ? g.act : (MODE == MODE_BF16_GELU ? TESS_ACT_GELU_ERF : TESS_ACT_NONE);
+    const int nvalid = g.N - col < 4 ? g.N - col : 4;
+    v += bias;
+    const int64_t o = (int64_t)row * g.ldo + col;
+    const bool full = vec && nvalid == 4;
+    if (preact) {
+        if (out_f32) {
+            float* p = (float*)g.preact + o;
+            if (full) *(floatx4*)p = v;
+            else for (int e = 0; e < nvalid; ++e) p[e] = v[e];
         } else {
-            static_for<16>([&](auto r) {
-                const int row = frow0 + 8 * (r / 4) + (r % 4);
-                if (row < g.M) out[(int64_t)row * g.ldo + col] = z[r];
-            });
+            uint16_t* p = (uint16_t*)g.preact + o;
+            const u32x2 w = pack_bf16x4(v);
+            if (full) *(u32x2*)p = w;
+            else for (int e = 0; e < nvalid; ++e) p[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+    if (act != TESS_ACT_NONE) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], act);
+    }
+    if (out_f32) {
+        float* p = (float*)g.out + o;
+        if (full) {
+            if (accumulate) v += *(const floatx4*)p;
+            *(floatx4*)p = v;
+        } else {
+            for (int e = 0; e < nvalid; ++e) p[e] = accumulate ? p[e] + v[e] : v[e];
         }
     } else {
-        uint16_t* out = (uint16_t*)g.out;
-        static_for<16>([&](auto r) {
-            const int row = frow0 + 8 * (r / 4) + (r % 4);
-            if (row < g.M) out[(int64_t)row * g.ldo + col] = f32_to_bf16_bits(z[r]);
-        });
+        uint16_t* p = (uint16_t*)g.out + o;
+        const u32x2 w = pack_bf16x4(v);
+        if (full) *(u32x2*)p = w;
+        else for (int e = 0; e < nvalid; ++e) p[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
     }
 }
 
@@ -427,6 +462,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#ifdef TESS_X_TIMING2
+    const long long T0 = clock64();
+    long long T1 = 0, T2 = 0;
+#define TESS_T2_DONE(slot) if (blockIdx.x == 37 && lane == 0 && g.ws) { ((long long*)g.ws)[wave * 8 + slot] = clock64() - T0; }
+#else
+#define TESS_T2_DONE(slot)
+#endif
     const int wm = wave / WGN, wn = wave % WGN;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int nb = tiles_m * tiles_n;
@@ -512,34 +554,39 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     // requests trickle out at the rate the texture path can take them
     LA la;
     LB lb;
+    // State of the tile being requested (captured by aim(), so that the requests that
+    // trickle out later do not see the pointers already advanced to the next tile).
     uint32_t rq_stage = 0;          // LDS address of the stage being filled
     uint32_t rq_asoff = 0, rq_bsoff = 0;   // K advance of that tile inside its panels
-    auto set_panels = [&]() {
-        const int t = ld_t < g.q ? ld_t : g.q - 1;
-        la.set_panel(ka->a[t]);
-        lb.set_panel(ka->b[t]);
-    };
-    auto advance = [&]() {
-        if (++ld_ks == kt_per_panel) {
-            ld_ks = 0;
-            ++ld_t;
-            set_panels();
-        }
-    };
+    u32x4 rq_rsrc_a = {0u, 0u, 0u, 0u}, rq_rsrc_b = {0u, 0u, 0u, 0u};
+    int rq_left = nkt;              // tiles not yet aimed at
     auto request = [&](auto it) {
-        if constexpr (it < LA::ITERS) la.request(it, rq_stage, wave_u, rq_asoff);
-        else lb.request(std::integral_constant<int, it - LA::ITERS>{}, rq_stage + A_BYTES, wave_u, rq_bsoff);
+        if constexpr (it < LA::ITERS) la.request(it, rq_rsrc_a, rq_stage, wave_u, rq_asoff);
+        else lb.request(std::integral_constant<int, it - LA::ITERS>{}, rq_rsrc_b, rq_stage + A_BYTES, wave_u, rq_bsoff);
     };
-    auto aim = [&](int stage) {     // point the requests at `stage` and the next tile
-        rq_stage = lds_base + stage * STAGE_BYTES;
-        rq_asoff = ld_ks * a_kstep;
-        rq_bsoff = ld_ks * b_kstep;
+    // Point the requests at LDS stage `stage` and the next tile of the K loop.  Past
+    // the end of the loop the last tile is requested again (into a slot nobody reads):
+    // every period then issues the same requests and the wait counts stay constant.
+    auto aim = [&](int stage) {
+        rq_stage = __builtin_amdgcn_readfirstlane(lds_base + stage * STAGE_BYTES);
+        rq_asoff = __builtin_amdgcn_readfirstlane(ld_ks * a_kstep);
+        rq_bsoff = __builtin_amdgcn_readfirstlane(ld_ks * b_kstep);
+        const int t = ld_t < g.q ? ld_t : g.q - 1;
+        rq_rsrc_a = LA::descriptor(ka->a[t]);
+        rq_rsrc_b = LB::descriptor(ka->b[t]);
+        if (rq_left > 1) {
+            --rq_left;
+            if (++ld_ks == kt_per_panel) { ld_ks = 0; ++ld_t; }
+        }
     };
     // with three or more stages a tile has more than a period to land and its requests
     // are spread over the whole period; with two stages they go out in the first half
-    constexpr int RQ_SPAN = NSTAGE >= 3 ? NSLOT : NSLOT / 2;
+#ifndef TESS_X_RQNUM
+#define TESS_X_RQNUM 2
+#endif
+    constexpr int RQ_SPAN = NSTAGE >= 3 ? NSLOT : NSLOT * TESS_X_RQNUM / 4;
     constexpr int STRIDE = RQ_SPAN / LOADS;
-    static_assert(RQ_SPAN % LOADS == 0 && STRIDE >= 1, "requests spaced evenly over the MFMA slots");
+    static_assert(STRIDE >= 1, "requests spaced evenly over the MFMA slots");
     auto request_at = [&](auto slot) {
         if constexpr (slot % STRIDE == 0 && slot / STRIDE < LOADS)
             request(std::integral_constant<int, slot / STRIDE>{});
@@ -570,78 +617,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     constexpr std::false_type no{};
 
     if constexpr (DIRECT) {
-        // Ring of NSTAGE LDS slots; tile r lives in slot r % NSTAGE.  All slots are
-        // requested up front.  Barrier r (every wave has read tile r, tile r+1 has
-        // landed) frees slot r % NSTAGE; tile r+NSTAGE is then requested into it,
-        // spread over the MFMAs up to barrier r+1.  It is needed at barrier
-        // r+NSTAGE-1, so its requests have NSTAGE-2 tile periods to complete.
+        // Ring of NSTAGE LDS slots; tile r lives in slot r % NSTAGE.  Barrier r (every
+        // wave has read tile r, tile r+1 has landed) frees slot r % NSTAGE; tile
+        // r+NSTAGE is then requested into it, its requests attached to the MFMAs that
+        // follow (the last k16 step of tile r, then the first steps of tile r+1).  One
+        // loop body serves the whole K range: see aim() for the tail.
         la.init(lane, wave_u, row0, g.M, g.lda);
         lb.init(lane, wave_u, col0, g.N, g.ldb);
-        set_panels();
-        static_for<NSTAGE>([&](auto s) {
-            if (s < nkt) {
+        constexpr int FIRST = (FM * FN + STRIDE - 1) / STRIDE < LOADS ? (FM * FN + STRIDE - 1) / STRIDE : LOADS;
+        if (nkt > 0) {
+            // tiles 0 .. NSTAGE-2 in bulk, and of tile NSTAGE-1 the requests that the
+            // last k16 step of a period would carry; the first body steps bring the rest
+            static_for<NSTAGE - 1>([&](auto s) {
                 aim(s);
                 static_for<LOADS>([&](auto it) { request(it); });
-                advance();
-            }
-        });
-        // tile 0 must have landed; the later ones may still be in flight
-        if (nkt >= NSTAGE) wait_vmcnt<(NSTAGE - 1) * LOADS>();
-        else wait_vmcnt<0>();
-        lds_barrier();
-        int stage = 0;
-        if (nkt > 0) {
+            });
+            aim(NSTAGE - 1);
+            static_for<FIRST>([&](auto it) { request(it); });
+            wait_vmcnt<(NSTAGE - 2) * LOADS + FIRST>();            // tile 0 has landed
+            lds_barrier();
             load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
-            body_steps(0, no);
         }
-        int r = 0;
-        // steady state: tile r+NSTAGE exists and is requested during period r
-        for (; r + NSTAGE < nkt; ++r) {
+        int stage = 0;
+        for (int r = 0; r < nkt; ++r) {
+            body_steps(stage, yes);
             const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
-#ifdef TESS_X_TIMING
-            const long long t0 = clock64();
-#endif
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of tile r are done
-#ifdef TESS_X_TIMING
-            const long long t1 = clock64();
-#endif
             wait_vmcnt<(NSTAGE - 2) * LOADS>();                    // tile r+1 has landed
-#ifdef TESS_X_TIMING
-            const long long t2 = clock64();
-#endif
             lds_barrier();                                         // barrier r
-#ifdef TESS_X_TIMING
-            const long long t3 = clock64();
-#endif
             aim(stage);
             last_step(next, yes, yes);
-#ifdef TESS_X_TIMING
-            const long long t4 = clock64();
-#endif
-            body_steps(next, yes);
-            advance();
-            stage = next;
-#ifdef TESS_X_TIMING
-            if (blockIdx.x == 37 && lane == 0 && r >= 16 && r < 16 + 64 && g.ws) {
-                long long* o = (long long*)g.ws + ((r - 16) * 8 + wave) * 8;
-                o[0] = t0; o[1] = t1; o[2] = t2; o[3] = t3; o[4] = t4; o[5] = clock64();
-            }
-#endif
-        }
-        // drain: nothing left to request
-        for (; r < nkt; ++r) {
-            const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            wait_vmcnt<0>();
-            lds_barrier();
-            if (r + 1 < nkt) {
-                last_step(next, yes, no);
-                body_steps(next, no);
-            } else {
-                last_step(next, no, no);
-            }
             stage = next;
         }
+        // the epilogue reuses the LDS: nothing may still be landing in it
+        wait_vmcnt<0>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        lds_barrier();
     } else {
         // register-staged double buffer with a zero-filled K tail
         SA sa_;
@@ -678,23 +689,81 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     }
 
     // ---- epilogue
+#ifdef TESS_X_TIMING2
+    T2 = clock64() - T0;
+#endif
     if (g.splits > 1) {
         // partial sums in accumulator order: [(z*nb + tile)][wave][frag][reg][lane]
         float* w = g.ws + ((size_t)blockIdx.z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
                    (size_t)wave * (FM * FN * 16 * 64) + lane;
         static_for<FM * FN>([&](auto f) {
             static_for<16>([&](auto r) { w[(f * 16 + r) * 64] = acc[f][r()]; });
+            __builtin_amdgcn_sched_barrier(0);
         });
         return;
     }
-    static_for<FN>([&](auto j) {
-        const int col = col0 + wn * WTN + j * 32 + (lane & 31);
-        const float bv = (g.bias && col < g.N) ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col]) : 0.0f;
-        static_for<FM>([&](auto i) {
-            const int frow0 = row0 + wm * WTM + i * 32 + 4 * (lane >> 5);
-            store_fragment(g, acc[i * FN + j], frow0, col, bv);
+    // The wavefront passes its accumulators through a private slice of the (now idle)
+    // LDS, half of its tile at a time, to turn the MFMA fragment layout into rows: a
+    // short rolled loop then handles four adjacent columns per lane, so every output
+    // row leaves as one contiguous run and the code stays small.
+    {
+        constexpr int HR = WTM / 2;                    // rows per half
+        constexpr int ROWB = WTN * 4;                  // fp32 bytes per row of the wave tile
+        constexpr int CPR = WTN / 4;                   // 16-byte chunks per row
+        constexpr int RPI = 64 / CPR;                  // rows per 64-lane pass
+        static_assert(FM % 2 == 0, "two halves of whole fragments");
+        static_assert(NSTAGE * STAGE_BYTES >= WGM * WGN * HR * ROWB, "LDS holds half a tile in fp32");
+        char* slice = lds + wave * (HR * ROWB);
+        const int esize = g.out_f32 ? 4 : 2;
+        const bool vec = ((g.ldo * esize) % 16 == 0) &&
+                         ((reinterpret_cast<uintptr_t>(g.out) & 15u) == 0) &&
+                         (!g.preact || (reinterpret_cast<uintptr_t>(g.preact) & 15u) == 0);
+        // chunk c of row r is kept at chunk c ^ (8 * bit 2 of r): the two half-waves of
+        // a fragment (rows r and r+4) then write to different banks
+        static_for<2>([&](auto half) {
+            static_for<FM / 2>([&](auto ii) {
+                static_for<FN>([&](auto j) {
+                    constexpr int f = (half * (FM / 2) + ii) * FN + j;
+                    const int cl = j * 32 + (lane & 31);
+                    static_for<16>([&](auto r) {
+                        const int rl = ii * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                        const int phys = (cl >> 2) ^ (((rl >> 2) & 1) << 3);
+                        *(float*)(slice + rl * ROWB + phys * 16 + (cl & 3) * 4) = acc[f][r()];
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            });
+            const int wrow0 = row0 + wm * WTM + half * HR, wcol0 = col0 + wn * WTN;
+            // a lane serves the same four columns in every pass: fetch their bias once
+            const int c = lane % CPR, col = wcol0 + c * 4;
+            floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
+            if (g.bias) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < g.N) bias4[e] = bf16_bits_to_f32(((const uint16_t*)g.bias)[col + e]);
+            }
+            auto drain = [&](auto mode) {
+#pragma unroll 4
+                for (int it = 0; it < HR / RPI; ++it) {
+                    const int rl = it * RPI + lane / CPR;
+                    const int phys = c ^ (((rl >> 2) & 1) << 3);
+                    const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
+                    const int row = wrow0 + rl;
+                    if (row < g.M && col < g.N) emit4<mode>(g, row, col, v, bias4, vec);
+                }
+            };
+            if (g.preact || g.act == TESS_ACT_GELU_TANH || (g.out_f32 && g.act != TESS_ACT_NONE))
+                drain(std::integral_constant<int, MODE_GENERIC>{});
+            else if (g.out_f32 && g.accumulate) drain(std::integral_constant<int, MODE_F32_ACC>{});
+            else if (g.out_f32) drain(std::integral_constant<int, MODE_F32>{});
+            else if (g.act == TESS_ACT_GELU_ERF) drain(std::integral_constant<int, MODE_BF16_GELU>{});
+            else drain(std::integral_constant<int, MODE_BF16>{});
+            __builtin_amdgcn_sched_barrier(0);
         });
-    });
+    }
+#ifdef TESS_X_TIMING2
+    if (blockIdx.x == 37 && lane == 0 && g.ws) { long long* o = (long long*)g.ws + wave * 8; o[0] = T1; o[1] = T2; o[2] = clock64() - T0; }
+#endif
 }
 
 // Sums the K-split partials in ascending split order and applies the epilogue.
