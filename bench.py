@@ -202,6 +202,17 @@ def main():
         print(f"unknown bf16 workload {args.workload}", file=sys.stderr)
         sys.exit(2)
 
+    # what the matrix cores sustain on this device at its actual clock (no memory traffic)
+    sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda:0")
+    B.probe_mfma_rate(sink, 256, 2000)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    probe_flop = B.probe_mfma_rate(sink, 256, 20000)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_only = probe_flop / e0.elapsed_time(e1) / 1e9
+
     res = time_workload(torch, tess, B, wl, w, args.steps, args.warmup, args.kernel_reps)
     # dominant kernel = the longest call that is ONE launch of the MFMA kernel (calls
     # with K splits also run a reduction kernel, so their event time covers two kernels)
@@ -224,6 +235,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "pct_of_bf16_mfma_peak": round(100.0 * res["tflops"] / PEAK_BF16_TFLOPS, 2),
+        "mfma_only_loop_tflops": round(mfma_only, 1),
+        "pct_of_mfma_only_loop": round(100.0 * res["tflops"] / mfma_only, 2),
         "config": {"workload": w.name, "grid": [w.q, w.q, w.d], "processor": [0, 0, 0],
                    "layers": {L.name: {"a": L.a, "b": L.b, "c": L.c, "block": [L.m, L.kb, L.n],
                                        "epilogue": L.act} for L in w.layers},

@@ -132,6 +132,13 @@ size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
 tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int32_t* tile_n,
                              int32_t* k_splits);
 
+/* Measurement aid: enqueues a register-resident loop of bf16 32x32x16 MFMAs (no
+ * memory traffic) on `workgroups` workgroups of 256 threads, `iters` x 8 MFMAs per
+ * wavefront, and writes one float per thread to `sink` (device, workgroups*256 floats)
+ * so that the loop is not optimised away.  Timing it gives the matrix-core rate this
+ * device sustains at its actual clock: workgroups * 4 * iters * 8 * 32768 flop.   */
+tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream);
+
 /* Validates a descriptor alone (grid rules and divisibility). */
 tess_status tess_desc_check(const tess_desc* desc);
 

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
 
 EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
-           "tess_linear_workspace_bytes", "tess_linear_plan", "tess_desc_check", "tess_block_shape",
+           "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate", "tess_desc_check", "tess_block_shape",
            "tess_status_string", "tess_version"]
 
 
@@ -62,6 +62,8 @@ def lib():
         i32p = ctypes.POINTER(ctypes.c_int32)
         L.tess_linear_plan.restype = cint
         L.tess_linear_plan.argtypes = [dp, cint, i32p, i32p, i32p]
+        L.tess_probe_mfma_rate.restype = cint
+        L.tess_probe_mfma_rate.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
         L.tess_desc_check.restype = cint
         L.tess_desc_check.argtypes = [dp]
         L.tess_block_shape.restype = cint
@@ -120,6 +122,17 @@ def plan(desc, op):
     if st:
         raise TessError(st, "tess_linear_plan")
     return tm.value, tn.value, ks.value
+
+
+def probe_mfma_rate(sink, workgroups, iters, stream=None):
+    """tess_probe_mfma_rate: enqueue the register-resident MFMA loop; returns its flop count."""
+    if sink.numel() < workgroups * 256 or sink.dtype != torch.float32 or not sink.is_cuda:
+        raise ValueError("sink: need a device float32 tensor of workgroups*256 elements")
+    st = lib().tess_probe_mfma_rate(ctypes.c_void_p(sink.data_ptr()), workgroups, iters,
+                                    _stream(stream))
+    if st:
+        raise TessError(st, "tess_probe_mfma_rate")
+    return workgroups * 4 * iters * 8 * 32768.0
 
 
 def _panel_array(panels, rows, cols, what):

@@ -24,37 +24,38 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
     p.path = Path::Mfma;
     const int64_t kt_total = (int64_t)q * ((Kp + BK_HOST - 1) / BK_HOST);
     p.direct = (Kp % BK_HOST == 0) ? 1 : 0;
-    // Tile and K-split are chosen with a small cost model in units of "one 64-deep
-    // stage of a 256 x 256 tile on one compute unit": a launch runs in rounds of 256
-    // workgroups, a workgroup costs its stages plus a fixed start/finish overhead, a
-    // 128 x 128 tile does a quarter of the work per stage at about half the
-    // efficiency (twice the panel traffic per flop), and every split adds one fp32
-    // partial tile to write and read back.
-    const double kOverheadStages = 6.0;
-    const double kPartialTileStages = 1.6;   // write + read of 256 KiB of partials
+    // Tile and K-split are chosen with a small cost model in microseconds, fitted to
+    // timings of this kernel on MI355X.  A launch runs in rounds of 256 workgroups (one
+    // per compute unit).  A workgroup costs a fixed start/finish time plus its 64-deep
+    // stages; a stage is slower the fuller the round is (shared clock and fabric).  A
+    // split adds a reduction launch that streams every fp32 partial tile once more.
+    struct TileCost { int t; double fixed_us, stage_idle_us, stage_full_us; };
+    const TileCost cands[2] = {{256, 10.0, 1.0, 1.6}, {128, 5.0, 0.36, 0.60}};
+    const double kLaunchUs = 4.0, kReduceLaunchUs = 2.0, kReduceBytesPerUs = 4.0e6;
     double best = 1e30;
-    const int cands[2] = {256, 128};
     for (int ci = 0; ci < 2; ++ci) {
-        const int t = cands[ci];
+        const TileCost& tc = cands[ci];
+        const int t = tc.t;
         // the register-staged loader (ragged K) only exists for the small tile
         if (t == 256 && !(p.direct && M >= 256 && N >= 256)) continue;
         const int64_t tiles = ((M + t - 1) / t) * ((N + t - 1) / t);
-        const double stage_cost = t == 256 ? 1.0 : 0.5;
-        const double partial_cost = t == 256 ? kPartialTileStages : kPartialTileStages / 4;
-        const int per_cu = t == 256 ? 1 : 2;              // resident workgroups per compute unit
         for (int sp = 1; sp <= 16; ++sp) {
             if (sp > 1 && kt_total / sp < 8) break;       // keep at least 8 stages per split
             const int64_t wgs = tiles * sp;
-            const int64_t rounds = (wgs + 256 * per_cu - 1) / (256 * per_cu);
             const double kt = (double)((kt_total + sp - 1) / sp);
-            double cost = rounds * per_cu * (kt * stage_cost + kOverheadStages * stage_cost);
-            if (sp > 1) cost += (double)sp * tiles * partial_cost / 256.0 + 2.0;
+            const int64_t full_rounds = wgs / 256, rem = wgs % 256;
+            double cost = kLaunchUs + (double)full_rounds * (tc.fixed_us + kt * tc.stage_full_us);
+            if (rem) {
+                const double fill = (double)rem / 256.0;
+                cost += tc.fixed_us + kt * (tc.stage_idle_us + fill * (tc.stage_full_us - tc.stage_idle_us));
+            }
+            if (sp > 1)
+                cost += kReduceLaunchUs + (double)wgs * t * t * sizeof(float) / kReduceBytesPerUs;
             if (cost < best) { best = cost; p.bm = p.bn = t; p.splits = sp; }
         }
     }
     const int64_t tiles = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
-    if (const char* e = getenv("TESS_BK")) p.bk = atoi(e) == 32 ? 32 : 64;   // tuning knobs
-    if (const char* e = getenv("TESS_WAVES")) p.waves = atoi(e) == 8 ? 8 : 4;
+    // tuning overrides, read at every call so that the workspace query and the launch agree
     if (const char* e = getenv("TESS_SPLITS")) { const int v = atoi(e); if (v >= 1 && kt_total / v >= 1) p.splits = v; }
     if (const char* e = getenv("TESS_TILE")) { const int v = atoi(e); if (v == 128 || (v == 256 && p.direct && M >= 256 && N >= 256)) p.bm = p.bn = v; }
     const int64_t tiles2 = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
@@ -118,9 +119,6 @@ static tess_status run(GemmArgs& g, void* workspace, size_t workspace_bytes, voi
         g.ws = static_cast<float*>(workspace);
     }
     g.splits = p.splits;
-#if defined(TESS_X_TIMING) || defined(TESS_X_TIMING2)
-    g.ws = static_cast<float*>(workspace);
-#endif
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = (p.path == Path::Mfma) ? launch_mfma(g, p, s) : launch_generic(g, s);
     return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
@@ -247,6 +245,15 @@ tess_status tess_linear_bwd_dw(const tess_desc* desc, const void* const* x_panel
     g.accumulate = accumulate;
     g.a_kc = 0; g.b_kc = 0; g.in_f32 = desc->in_dtype == TESS_F32;
     return run(g, workspace, workspace_bytes, hip_stream);
+}
+
+tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream)
+{
+    if (!sink) return TESS_ERR_NULL;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1) return TESS_ERR_SHAPE;
+    hipError_t e = launch_mfma_probe(static_cast<float*>(sink), workgroups, iters,
+                                     static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
 }
 
 const char* tess_status_string(int status)

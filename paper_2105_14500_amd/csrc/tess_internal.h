@@ -58,5 +58,6 @@ Plan make_plan(const GemmArgs& g);
 // Enqueue; returns hipSuccess or the launch error.
 hipError_t launch_generic(const GemmArgs& g, hipStream_t s);
 hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s);
+hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, hipStream_t s);
 
 }  // namespace tess

@@ -185,9 +185,6 @@ __device__ __forceinline__ void static_for(F&& f)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
-#ifdef TESS_X_NOWAIT
-    if (N >= 0) return;
-#endif
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
@@ -195,9 +192,6 @@ __device__ __forceinline__ void wait_vmcnt()
 // still in flight for later stages are not waited for.
 __device__ __forceinline__ void lds_barrier()
 {
-#ifdef TESS_X_NOBARRIER
-    return;
-#endif
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
@@ -268,23 +262,17 @@ struct DmaLoader {
     __device__ __forceinline__ void request(IT it, const u32x4& rsrc, uint32_t lds_stage, int wave_u,
                                             uint32_t soff) const
     {
-#ifdef TESS_X_NOLOADS
-        if (lds_stage != 0xffffffffu) return;
-#endif
         if constexpr (it % 4 == 0) {
             const uint32_t m0 = lds_stage + (uint32_t)(wave_u * ITERS + it) * 1024u;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(m0) : "m0", "memory");
         }
-#ifndef TESS_X_POLICY
-#define TESS_X_POLICY ""
-#endif
         // the descriptor must sit in scalar registers whatever the optimizer did to it
         u32x4 d;
         d[0] = __builtin_amdgcn_readfirstlane(rsrc[0]);
         d[1] = __builtin_amdgcn_readfirstlane(rsrc[1]);
         d[2] = __builtin_amdgcn_readfirstlane(rsrc[2]);
         d[3] = __builtin_amdgcn_readfirstlane(rsrc[3]);
-        asm volatile("buffer_load_dwordx4 %0, %1, %2 offen offset:%3" TESS_X_POLICY " lds"
+        asm volatile("buffer_load_dwordx4 %0, %1, %2 offen offset:%3 lds"
                      :
                      : "v"(off[it]), "s"(d), "s"(soff), "n"((it % 4) * 1024)
                      : "memory");
@@ -462,13 +450,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-#ifdef TESS_X_TIMING2
-    const long long T0 = clock64();
-    long long T1 = 0, T2 = 0;
-#define TESS_T2_DONE(slot) if (blockIdx.x == 37 && lane == 0 && g.ws) { ((long long*)g.ws)[wave * 8 + slot] = clock64() - T0; }
-#else
-#define TESS_T2_DONE(slot)
-#endif
     const int wm = wave / WGN, wn = wave % WGN;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int nb = tiles_m * tiles_n;
@@ -520,9 +501,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     // Fragment u of a k16 step: the FN fragments of B first, then the FM of A (the
     // first MFMAs of a step need af[0] and every bfr[j]).
     auto load_frag = [&](auto buf, int stage, auto kk, auto u) {
-#ifdef TESS_X_NOREADS
-        if (stage >= 0) return;
-#endif
         const char* sa = lds + stage * STAGE_BYTES;
         if constexpr (u < FN) bfr[buf][u] = rb.read(sa + A_BYTES, u, kk);
         else af[buf][u - FN] = ra.read(sa, u - FN, kk);
@@ -537,11 +515,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     auto mfma_step = [&](auto buf, auto&& side) {
         static_for<FM * FN>([&](auto x) {
             constexpr int i = x / FN, j = x % FN;
-#ifdef TESS_X_NOMFMA
-            if (x == 0) acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[x], 0, 0, 0);
-#else
             acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[x], 0, 0, 0);
-#endif
             side(x);
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -581,10 +555,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     };
     // with three or more stages a tile has more than a period to land and its requests
     // are spread over the whole period; with two stages they go out in the first half
-#ifndef TESS_X_RQNUM
-#define TESS_X_RQNUM 2
-#endif
-    constexpr int RQ_SPAN = NSTAGE >= 3 ? NSLOT : NSLOT * TESS_X_RQNUM / 4;
+    constexpr int RQ_SPAN = NSTAGE >= 3 ? NSLOT : NSLOT / 2;
     constexpr int STRIDE = RQ_SPAN / LOADS;
     static_assert(STRIDE >= 1, "requests spaced evenly over the MFMA slots");
     auto request_at = [&](auto slot) {
@@ -689,9 +660,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     }
 
     // ---- epilogue
-#ifdef TESS_X_TIMING2
-    T2 = clock64() - T0;
-#endif
     if (g.splits > 1) {
         // partial sums in accumulator order: [(z*nb + tile)][wave][frag][reg][lane]
         float* w = g.ws + ((size_t)blockIdx.z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
@@ -761,9 +729,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             __builtin_amdgcn_sched_barrier(0);
         });
     }
-#ifdef TESS_X_TIMING2
-    if (blockIdx.x == 37 && lane == 0 && g.ws) { long long* o = (long long*)g.ws + wave * 8; o[0] = T1; o[1] = T2; o[2] = clock64() - T0; }
-#endif
 }
 
 // Sums the K-split partials in ascending split order and applies the epilogue.
@@ -845,20 +810,41 @@ static hipError_t launch_layout(const GemmArgs& g, const Plan& p, hipStream_t s)
     return hipErrorInvalidValue;
 }
 
+// Register-resident MFMA loop: 8 independent accumulator chains per wavefront.
+__global__ __launch_bounds__(256) void tess_mfma_probe_kernel(float* sink, int iters)
+{
+    bf16x8 a, b;
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(float)((threadIdx.x + e) % 7 - 3);
+        b[e] = (__bf16)(float)((threadIdx.x * 3 + e) % 5 - 2);
+    }
+    floatx16 c[8];
+    for (int i = 0; i < 8; ++i)
+        for (int r = 0; r < 16; ++r) c[i][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[i], 0, 0, 0);
+    }
+    float sum = 0.0f;
+    for (int i = 0; i < 8; ++i)
+        for (int r = 0; r < 16; ++r) sum += c[i][r];
+    sink[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, hipStream_t s)
+{
+    hipLaunchKernelGGL(tess_mfma_probe_kernel, dim3(workgroups), dim3(256), 0, s, sink, iters);
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     if (p.bm == 256 && p.bn == 256) {
         if (!p.direct) return hipErrorInvalidValue;
-        if (p.bk == 32) {
-            if (p.waves == 4) return launch_layout<256, 256, 32, 4, 2, 2, true>(g, p, s);
-            return launch_layout<256, 256, 32, 4, 2, 4, true>(g, p, s);
-        }
-        if (p.waves == 4) return launch_layout<256, 256, 64, 2, 2, 2, true>(g, p, s);
-        return launch_layout<256, 256, 64, 2, 2, 4, true>(g, p, s);
+        return launch_layout<256, 256, 64, 2, 2, 2, true>(g, p, s);
     }
     if (p.bm == 128 && p.bn == 128) {
         if (!p.direct) return launch_layout<128, 128, 64, 2, 2, 2, false>(g, p, s);
-        if (p.bk == 32) return launch_layout<128, 128, 32, 4, 2, 2, true>(g, p, s);
         return launch_layout<128, 128, 64, 3, 2, 2, true>(g, p, s);
     }
     return hipErrorInvalidValue;

@@ -151,3 +151,12 @@ def test_empty_and_error_paths_leave_outputs_untouched():
     assert ei.value.status == 2
     torch.cuda.synchronize()
     assert torch.all(y == 7.0)
+
+
+def test_mfma_rate_probe_runs():
+    """The measurement loop launches, fills its sink and reports its flop count."""
+    sink = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda:0")
+    flop = B.probe_mfma_rate(sink, 8, 10)
+    torch.cuda.synchronize()
+    assert flop == 8 * 4 * 10 * 8 * 32768.0
+    assert torch.isfinite(sink).all()
