@@ -29,6 +29,24 @@ __device__ __forceinline__ float gelu_erf_f(float x)
 {
     return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
 }
+// GELU (erf form) for 2-byte outputs, branch-free and about half the instructions of
+// the library erf: with z = |x|/sqrt(2) and t = 1/(1 + p z), the rational-exponential
+// approximation of Abramowitz & Stegun 7.1.26 gives erfc(z) = poly(t) exp(-z^2) with
+// absolute error below 1.5e-7.  1 + erf(x/sqrt(2)) is erfc(z) for x < 0 (no cancellation
+// in the tail) and 2 - erfc(z) otherwise.
+__device__ __forceinline__ float gelu_erf_fast(float x)
+{
+    const float z = __builtin_fabsf(x) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
+    float p = __builtin_fmaf(1.061405429f, t, -1.453152027f);
+    p = __builtin_fmaf(p, t, 1.421413741f);
+    p = __builtin_fmaf(p, t, -0.284496736f);
+    p = __builtin_fmaf(p, t, 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(x * x * -0.72134752044448170368f);   // exp(-x^2/2)
+    const float erfc_z = p * t * e;
+    const float one_plus_erf = x < 0.0f ? erfc_z : 2.0f - erfc_z;
+    return 0.5f * x * one_plus_erf;
+}
 __device__ __forceinline__ float gelu_tanh_f(float x)
 {
     const float c = 0.79788456080286535588f;
@@ -397,8 +415,13 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
         }
     }
     if (act != TESS_ACT_NONE) {
+        if (MODE == MODE_BF16_GELU) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], act);
+            for (int e = 0; e < 4; ++e) v[e] = gelu_erf_fast(v[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], act);
+        }
     }
     if (out_f32) {
         float* p = (float*)g.out + o;

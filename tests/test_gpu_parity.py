@@ -80,11 +80,36 @@ def test_bf16_output_is_rne_of_fp32_result():
     the round-to-nearest-even of the same kernel's fp32 output."""
     q, d, m, kb, n = 2, 2, 256, 128, 256
     inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=5, w_std=0.1)
-    g32 = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "f32", act="gelu_erf")
-    g16 = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "bf16", act="gelu_erf")
+    g32 = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "f32")
+    g16 = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "bf16")
     for key in ("y", "dx", "dw"):
         want = orc.round_bf16(g32[key].numpy())
         assert np.array_equal(f64(g16[key]), want), key
+
+
+def test_gelu_of_exact_preactivations_bf16_out():
+    """The 2-byte-output GELU epilogue on pre-activations that carry no rounding: inputs are
+    multiples of 1/8 and weights are -1, 0, 1, so every sum is exact in fp32 and the only
+    arithmetic left is the kernel's erf, whose absolute error is below 1e-6.  Against the
+    fp64 definition rounded to bf16 the output may therefore differ by one bf16 step where
+    the exact value sits next to a rounding boundary (plus that 1e-6 in the far negative
+    tail, where a bf16 step is smaller still), nowhere by more, and only rarely."""
+    q, d, m, kb, n = 2, 2, 256, 128, 256
+    r = np.random.default_rng(11)
+    x = torch.tensor(r.integers(-4, 5, size=(q, m, kb)) / 8.0, dtype=torch.bfloat16)
+    w = torch.tensor(r.integers(-1, 2, size=(q, kb, n)).astype(np.float64), dtype=torch.bfloat16)
+    bias = torch.tensor(r.integers(-8, 9, size=(n,)) / 8.0, dtype=torch.bfloat16)
+    dy = torch.zeros((q, m, n), dtype=torch.bfloat16)
+    got = f64(run_share(q, d, x, w, bias, dy, "bf16", "bf16", act="gelu_erf")["y"])
+    y, z = orc.fwd_panels([f64(x[t]) for t in range(q)], [f64(w[t]) for t in range(q)],
+                          bias=f64(bias), act=orc.ACT_GELU_ERF, want_z=True)
+    assert np.abs(z).max() >= 6.0 and np.abs(z).min() == 0.0          # both tails and the middle
+    want = orc.round_bf16(y)
+    step = np.maximum(np.abs(want), 2.0 ** -126) * 2.0 ** -7             # >= one bf16 step at |want|
+    assert np.all(np.abs(got - want) <= step + 1e-6)
+    body = np.abs(want) >= 1e-2
+    assert body.mean() > 0.5 and np.mean(got[body] != want[body]) < 5e-3
+    assert rel_err(got, y) <= 3e-3                                       # bf16 rounding alone
 
 
 @pytest.mark.parametrize("dtype,dims", [("bf16", (2, 2, 128, 64, 128)), ("bf16", (3, 3, 24, 40, 56)),
