@@ -31,7 +31,6 @@ def parse():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--all", action="store_true", help="also time every other bf16 workload")
-    ap.add_argument("--kernel-reps", type=int, default=10)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -79,7 +78,7 @@ class LayerState:
                                 workspace=self.ws)
 
 
-def time_workload(torch, tess, B, wl, w, steps, warmup, kernel_reps):
+def time_workload(torch, tess, B, wl, w, steps, warmup):
     layers = []
     for li, L in enumerate(w.layers):
         per_set = 2 * w.q * (L.m * L.kb + L.kb * L.n + L.m * L.n) + 2 * (L.m * L.n + L.m * L.kb) \
@@ -87,37 +86,41 @@ def time_workload(torch, tess, B, wl, w, steps, warmup, kernel_reps):
         sets = 1 if per_set >= 400e6 else max(2, int(600e6 // per_set))
         layers.append(LayerState(torch, tess, B, wl, w, L, seed=1000 * li, sets=min(sets, 8)))
 
-    def step(s):
+    names = ("fwd", "dx", "dw")
+
+    def step(s, marks=None):
         for st in layers:
-            st.fwd(s)
-            st.dx(s)
-            st.dw(s)
+            for name in names:
+                if marks is not None:
+                    e = torch.cuda.Event(enable_timing=True)
+                    e.record()
+                    marks.append(e)
+                getattr(st, name)(s)
+        if marks is not None:
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            marks.append(e)
 
     for s in range(warmup):
         step(s)
     torch.cuda.synchronize()
+    # the timed region: K steps, with one HIP event on the launch stream at every call
+    # boundary so that each call's average duration comes from these same launches
+    marks = [[] for _ in range(steps)]
     t0 = time.perf_counter()
     for s in range(steps):
-        step(s)
+        step(s, marks[s])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     flops_step = sum(3.0 * st.flops_call for st in layers)
     ms_step = dt / steps * 1e3
 
-    # per-call timing with HIP events on the launch stream
     calls = {}
+    ci = 0
     for st in layers:
-        for name in ("fwd", "dx", "dw"):
-            fn = getattr(st, name)
-            fn(0)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for s in range(kernel_reps):
-                fn(s)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / kernel_reps
+        for name in names:
+            ms = sum(m[ci].elapsed_time(m[ci + 1]) for m in marks) / steps
+            ci += 1
             M, N, K = {"fwd": (st.L.m, st.L.n, st.L.kb * w.q), "dx": (st.L.m, st.L.kb, st.L.n * w.q),
                        "dw": (st.L.kb, st.L.n, st.L.m * w.q)}[name]
             tm, tn, ks = tess.plan(st.desc, {"fwd": B.OP_FWD, "dx": B.OP_BWD_DX, "dw": B.OP_BWD_DW}[name])
@@ -213,12 +216,15 @@ def main():
     torch.cuda.synchronize()
     mfma_only = probe_flop / e0.elapsed_time(e1) / 1e9
 
-    res = time_workload(torch, tess, B, wl, w, args.steps, args.warmup, args.kernel_reps)
-    # dominant kernel = the longest call that is ONE launch of the MFMA kernel (calls
-    # with K splits also run a reduction kernel, so their event time covers two kernels)
+    res = time_workload(torch, tess, B, wl, w, args.steps, args.warmup)
+    # dominant kernel = the call with the most flops that is ONE launch of the MFMA kernel
+    # (calls with K splits also run a reduction kernel, so their event time covers two
+    # kernels); among equals the first listed, i.e. the forward call, whose launch shape is
+    # unique in a kernel trace
     single = {k: v for k, v in res["calls"].items() if v["k_splits"] == 1} or res["calls"]
-    dom_name, dom = max(single.items(), key=lambda kv: kv[1]["ms"])
-    dom_layer = next(st for st in res["layers"] if dom_name.startswith(st.L.name + "."))
+    layer_of = lambda name: next(st for st in res["layers"] if name.startswith(st.L.name + "."))
+    dom_name = max(single, key=lambda name: layer_of(name).flops_call)
+    dom, dom_layer = single[dom_name], layer_of(dom_name)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_cfg4.txt")
     if os.path.exists(tpath):
@@ -257,7 +263,7 @@ def main():
             if ow.dtype != "bf16" or ow.name == w.name:
                 continue
             torch.cuda.empty_cache()
-            r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, args.kernel_reps)
+            r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup)
             others[ow.name] = {"tflops": round(r["tflops"], 2),
                                "pct_peak": round(100.0 * r["tflops"] / PEAK_BF16_TFLOPS, 2),
                                "ms_per_step": round(r["ms_per_step"], 4), "calls": r["calls"]}
