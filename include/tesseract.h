@@ -139,6 +139,12 @@ tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int
  * device sustains at its actual clock: workgroups * 4 * iters * 8 * 32768 flop.   */
 tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream);
 
+/* Diagnostic: the output tile (tile row *tm, tile column *tn) that workgroup `block` of
+ * a launch over a tiles_m x tiles_n tile grid computes.  The same function the kernels
+ * use; a bijection from [0, tiles_m*tiles_n) onto the grid.  Pure host arithmetic. */
+tess_status tess_tile_of_block(int32_t block, int32_t tiles_m, int32_t tiles_n, int32_t* tm,
+                               int32_t* tn);
+
 /* Validates a descriptor alone (grid rules and divisibility). */
 tess_status tess_desc_check(const tess_desc* desc);
 

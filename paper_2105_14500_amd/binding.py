@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
 
 EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
-           "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate", "tess_desc_check", "tess_block_shape",
+           "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate", "tess_tile_of_block", "tess_desc_check", "tess_block_shape",
            "tess_status_string", "tess_version"]
 
 
@@ -64,6 +64,8 @@ def lib():
         L.tess_linear_plan.argtypes = [dp, cint, i32p, i32p, i32p]
         L.tess_probe_mfma_rate.restype = cint
         L.tess_probe_mfma_rate.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
+        L.tess_tile_of_block.restype = cint
+        L.tess_tile_of_block.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_int32)] * 2
         L.tess_desc_check.restype = cint
         L.tess_desc_check.argtypes = [dp]
         L.tess_block_shape.restype = cint
@@ -122,6 +124,15 @@ def plan(desc, op):
     if st:
         raise TessError(st, "tess_linear_plan")
     return tm.value, tn.value, ks.value
+
+
+def tile_of_block(block, tiles_m, tiles_n):
+    """tess_tile_of_block: (tile row, tile column) of one workgroup."""
+    tm, tn = ctypes.c_int32(), ctypes.c_int32()
+    st = lib().tess_tile_of_block(block, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn))
+    if st:
+        raise TessError(st, "tess_tile_of_block")
+    return tm.value, tn.value
 
 
 def probe_mfma_rate(sink, workgroups, iters, stream=None):

@@ -256,6 +256,19 @@ tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, 
     return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
 }
 
+tess_status tess_tile_of_block(int32_t block, int32_t tiles_m, int32_t tiles_n, int32_t* tm,
+                               int32_t* tn)
+{
+    if (!tm || !tn) return TESS_ERR_NULL;
+    if (tiles_m < 1 || tiles_n < 1 || tiles_m > 32768 || tiles_n > 32768) return TESS_ERR_SHAPE;
+    if (block < 0 || (int64_t)block >= (int64_t)tiles_m * tiles_n) return TESS_ERR_SHAPE;
+    int r, c;
+    tile_of_block(block, tiles_m, tiles_n, r, c);
+    *tm = r;
+    *tn = c;
+    return TESS_OK;
+}
+
 const char* tess_status_string(int status)
 {
     switch (status) {

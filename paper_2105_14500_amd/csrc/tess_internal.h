@@ -39,6 +39,26 @@ struct GemmArgs {
     float* ws;
 };
 
+// Block -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each with its
+// own L2: the block ids that land on one XCD are relabelled to a contiguous run of tile
+// ids, and tile ids walk bands of 8 tile rows column by column, so that the 32 tiles an
+// XCD has in flight share 8 row panels and 4 column panels in its L2.  A bijection from
+// [0, tiles_m*tiles_n) onto the tile grid for every grid size.
+__host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
+{
+    const int nb = tiles_m * tiles_n;
+    const int per = nb >> 3, rem = nb & 7;
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int lid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+    constexpr int GM = 8;
+    const int band = lid / (GM * tiles_n);
+    const int first = band * GM;
+    const int rows = tiles_m - first < GM ? tiles_m - first : GM;
+    const int in_band = lid - band * GM * tiles_n;
+    tm = first + in_band % rows;
+    tn = in_band / rows;
+}
+
 // Kernel families.
 enum class Path : int32_t { Generic = 0, Mfma = 1 };
 

@@ -439,25 +439,6 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
     }
 }
 
-// Block -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each with
-// its own L2: relabel so that one XCD gets a contiguous run of tile ids, and walk the
-// tiles in bands of 8 tile-rows so that a run shares A and B panels.
-__device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
-{
-    const int nb = tiles_m * tiles_n;
-    const int per = nb >> 3, rem = nb & 7;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int lid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
-    constexpr int GM = 8;
-    const int band = lid / (GM * tiles_n);
-    const int first = band * GM;
-    const int rows = tiles_m - first < GM ? tiles_m - first : GM;
-    const int in_band = lid - band * GM * tiles_n;
-    tm = first + in_band % rows;
-    tn = in_band / rows;
-}
-
-
 // WGM x WGN wavefronts tile the BM x BN macro tile; each owns (BM/WGM) x (BN/WGN).
 template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT>
 __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
@@ -477,7 +458,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int nb = tiles_m * tiles_n;
     int tm, tn;
-    block_to_tile(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int row0 = tm * BM, col0 = tn * BN;
 
     // ---- K range of this block (split over gridDim.z in whole stages)

@@ -115,3 +115,27 @@ def test_partition_helpers_match_block_table():
         assert torch.equal(a_p[j], want)
     with pytest.raises(ValueError):
         P.block_dims(2, 3, 12, 4, 4)
+
+
+@pytest.mark.parametrize("tiles_m,tiles_n", [(1, 1), (1, 7), (5, 3), (8, 8), (16, 16), (17, 16), (16, 17),
+                                             (32, 24), (32, 8), (8, 24), (33, 35), (3, 50), (50, 3),
+                                             (31, 47), (64, 5)])
+def test_block_to_tile_map_is_a_bijection(tiles_m, tiles_n):
+    seen = set()
+    for b in range(tiles_m * tiles_n):
+        tm, tn = B.tile_of_block(b, tiles_m, tiles_n)
+        assert 0 <= tm < tiles_m and 0 <= tn < tiles_n
+        seen.add((tm, tn))
+    assert len(seen) == tiles_m * tiles_n
+
+
+def test_block_to_tile_map_gives_each_xcd_a_compact_block():
+    """Of 256 consecutive workgroups (one per compute unit) of a 32 x 24 tile grid, the 32
+    that land on one XCD (every eighth block id) cover 8 tile rows x 4 tile columns."""
+    for rnd in range(3):
+        tiles = [B.tile_of_block(b, 32, 24) for b in range(256 * rnd, 256 * (rnd + 1))]
+        for xcd in range(8):
+            mine = tiles[xcd::8]
+            assert len(set(mine)) == 32
+            assert len({t[0] for t in mine}) == 8 and len({t[1] for t in mine}) == 4
+    assert B.lib().tess_tile_of_block(32 * 24, 32, 24, None, None) != 0
