@@ -21,7 +21,9 @@
  * identity <dY, XW> = <dX, X> = <dW, W>, one-hot inputs that expose the block
  * map h = i + k*q, the hand-written partition table under tests/golden/,
  * exact small-integer products, textbook values of the normal CDF for GELU,
- * and bit-level ties for the bf16 rounding helper.
+ * bit-level ties for the bf16 rounding helper, central differences of the
+ * (pinned) GELU forms and the location of GELU's minimum for the derivatives,
+ * and the total-sum and all-ones identities for the bias gradient.
  *
  * Build: gcc -O2 -fopenmp -fPIC -shared -o libtess_oracle.so tess_oracle.c -lm
  */
@@ -58,6 +60,34 @@ double orc_gelu_tanh(double x)
     const double pi = 3.14159265358979323846;
     const double c = sqrt(2.0 / pi);
     return 0.5 * x * (1.0 + tanh(c * (x + 0.044715 * x * x * x)));
+}
+
+/* Derivatives of the two GELU forms (product and chain rule on the definitions
+ * above): d/dx [x Phi(x)] = Phi(x) + x phi(x) with phi the standard normal
+ * density; for the tanh form, with u = c (x + 0.044715 x^3):
+ * 0.5 (1 + tanh u) + 0.5 x (1 - tanh^2 u) c (1 + 3 * 0.044715 x^2).          */
+double orc_gelu_erf_grad(double x)
+{
+    const double pi = 3.14159265358979323846;
+    const double Phi = 0.5 * (1.0 + erf(x / sqrt(2.0)));
+    const double phi = exp(-0.5 * x * x) / sqrt(2.0 * pi);
+    return Phi + x * phi;
+}
+
+double orc_gelu_tanh_grad(double x)
+{
+    const double pi = 3.14159265358979323846;
+    const double c = sqrt(2.0 / pi);
+    const double u = c * (x + 0.044715 * x * x * x);
+    const double th = tanh(u);
+    return 0.5 * (1.0 + th) + 0.5 * x * (1.0 - th * th) * c * (1.0 + 3.0 * 0.044715 * x * x);
+}
+
+static double orc_act_grad(double x, int act)
+{
+    if (act == ORC_ACT_GELU_ERF) return orc_gelu_erf_grad(x);
+    if (act == ORC_ACT_GELU_TANH) return orc_gelu_tanh_grad(x);
+    return 1.0;
 }
 
 static double orc_act(double x, int act)
@@ -217,6 +247,43 @@ void orc_bwd_dx_panels(int q, int64_t m, int64_t kb, int64_t n,
             }
             dx_out[rr * kb + u] = acc;
         }
+    }
+}
+
+/* Input gradient followed by the backward of the activation that produced the
+ * layer's input (the MLP's middle activation, Section 2.4): with Z the
+ * pre-activation that the previous linear layer saved, [m,kb],
+ *   dZ[r,u] = dX[r,u] * act'(Z[r,u]),   dX as in orc_bwd_dx_panels.          */
+void orc_bwd_dx_act_panels(int q, int64_t m, int64_t kb, int64_t n,
+                           const double* const* dy_panels, int64_t lddy,
+                           const double* const* w_panels, int64_t ldw,
+                           const double* z, int64_t ldz, int act,
+                           const int64_t* rows, int64_t n_rows, double* dz_out)
+{
+    orc_bwd_dx_panels(q, m, kb, n, dy_panels, lddy, w_panels, ldw, rows, n_rows, dz_out);
+    const int64_t R = rows ? n_rows : m;
+    for (int64_t rr = 0; rr < R; ++rr) {
+        const int64_t r = rows ? rows[rr] : rr;
+        for (int64_t u = 0; u < kb; ++u) dz_out[rr * kb + u] *= orc_act_grad(z[r * ldz + u], act);
+    }
+}
+
+/* Bias gradient.  The forward adds bias_j to every row of every block of block
+ * column j (Section 3.2, bias-add); its gradient is therefore the sum of dY
+ * over all those rows, which the paper collects on grid row 0 by a reduction
+ * along the column.  The q panels dY_{t,j,k} of one depth layer are exactly the
+ * blocks of that column, so
+ *   db[s] = sum_{t<q} sum_{r<m} dY_t[r,s]
+ * is what row 0 holds for depth layer k; `accumulate` adds further layers.   */
+void orc_bias_grad_panels(int q, int64_t m, int64_t n,
+                          const double* const* dy_panels, int64_t lddy,
+                          int accumulate, double* db_out)
+{
+    for (int64_t s = 0; s < n; ++s) {
+        double acc = 0.0;
+        for (int t = 0; t < q; ++t)
+            for (int64_t r = 0; r < m; ++r) acc += dy_panels[t][r * lddy + s];
+        db_out[s] = accumulate ? db_out[s] + acc : acc;
     }
 }
 

@@ -28,6 +28,9 @@ def lib():
         L.orc_gelu_erf.argtypes = [ctypes.c_double]
         L.orc_gelu_tanh.restype = ctypes.c_double
         L.orc_gelu_tanh.argtypes = [ctypes.c_double]
+        for name in ("orc_gelu_erf_grad", "orc_gelu_tanh_grad"):
+            getattr(L, name).restype = ctypes.c_double
+            getattr(L, name).argtypes = [ctypes.c_double]
         L.orc_round_bf16_scalar.restype = ctypes.c_float
         L.orc_round_bf16_scalar.argtypes = [ctypes.c_float]
         L.orc_round_bf16.argtypes = [ctypes.POINTER(ctypes.c_float), dp, i64]
@@ -49,6 +52,11 @@ def lib():
         L.orc_bwd_dw_panels.argtypes = [ctypes.c_int, i64, i64, i64, pp, i64, pp, i64,
                                         ip, i64, ctypes.c_int, dp]
         L.orc_bwd_dw_panels.restype = None
+        L.orc_bwd_dx_act_panels.argtypes = [ctypes.c_int, i64, i64, i64, pp, i64, pp, i64,
+                                            dp, i64, ctypes.c_int, ctypes.POINTER(i64), i64, dp]
+        L.orc_bwd_dx_act_panels.restype = None
+        L.orc_bias_grad_panels.argtypes = [ctypes.c_int, i64, i64, pp, i64, ctypes.c_int, dp]
+        L.orc_bias_grad_panels.restype = None
         L.orc_tess_fwd.argtypes = [ctypes.c_int] * 5 + [i64] * 3 + [dp, dp, dp, ctypes.c_int,
                                                                    dp, dp]
         L.orc_tess_fwd.restype = ctypes.c_int
@@ -78,12 +86,28 @@ def num_threads():
     return lib().orc_num_threads()
 
 
+def _scalar_fn(name, x):
+    """Apply a double -> double routine of the library to a scalar or element-wise."""
+    f = getattr(lib(), name)
+    if np.ndim(x) == 0:
+        return f(float(x))
+    return np.vectorize(f, otypes=[np.float64])(x)
+
+
 def gelu_erf(x):
-    return lib().orc_gelu_erf(float(x))
+    return _scalar_fn("orc_gelu_erf", x)
 
 
 def gelu_tanh(x):
-    return lib().orc_gelu_tanh(float(x))
+    return _scalar_fn("orc_gelu_tanh", x)
+
+
+def gelu_erf_grad(x):
+    return _scalar_fn("orc_gelu_erf_grad", x)
+
+
+def gelu_tanh_grad(x):
+    return _scalar_fn("orc_gelu_tanh_grad", x)
 
 
 def round_bf16(x):
@@ -181,6 +205,39 @@ def bwd_dx_panels(dy_panels, w_panels, rows=None):
     dx = np.empty((R, kb))
     lib().orc_bwd_dx_panels(q, m, kb, n, dyp, lddy, wp, ldw, rp, nr, _p(dx))
     return dx
+
+
+def bwd_dx_act_panels(dy_panels, w_panels, z, act, rows=None):
+    """dX of bwd_dx_panels times act'(z); z is the FULL [m, kb] pre-activation."""
+    q = len(dy_panels)
+    m, n = dy_panels[0].shape
+    kb = w_panels[0].shape[0]
+    assert all(p.shape == (m, n) for p in dy_panels) and all(p.shape == (kb, n) for p in w_panels)
+    z = _f64(z)
+    assert z.shape == (m, kb)
+    dyp, lddy = _panel_ptrs(dy_panels)
+    wp, ldw = _panel_ptrs(w_panels)
+    rp, nr, keep = _rows(rows)
+    R = nr if rows is not None else m
+    dz = np.empty((R, kb))
+    lib().orc_bwd_dx_act_panels(q, m, kb, n, dyp, lddy, wp, ldw, _p(z), kb, act, rp, nr, _p(dz))
+    return dz
+
+
+def bias_grad_panels(dy_panels, accumulate_into=None):
+    q = len(dy_panels)
+    m, n = dy_panels[0].shape
+    assert all(p.shape == (m, n) for p in dy_panels)
+    dyp, lddy = _panel_ptrs(dy_panels)
+    if accumulate_into is not None:
+        db = accumulate_into
+        assert db.dtype == np.float64 and db.shape == (n,) and db.flags.c_contiguous
+        acc = 1
+    else:
+        db = np.empty((n,))
+        acc = 0
+    lib().orc_bias_grad_panels(q, m, n, dyp, lddy, acc, _p(db))
+    return db
 
 
 def bwd_dw_panels(x_panels, dy_panels, rows=None, accumulate_into=None):

@@ -368,3 +368,101 @@ def test_planted_mistakes_are_caught():
         if not np.allclose(blk, full[h_bad * m:(h_bad + 1) * m, j * n:(j + 1) * n]):
             wrong += 1
     assert wrong > 0
+
+
+# ------------------------------------------------- backward epilogues next to the path
+def test_gelu_derivatives_against_central_differences():
+    """The derivative formulas against central differences of the GELU forms that the
+    tests above pin (step 1e-5: truncation ~1e-11, rounding ~1e-11)."""
+    h = 1e-5
+    for x in np.linspace(-6.0, 6.0, 97):
+        fd = (orc.gelu_erf(x + h) - orc.gelu_erf(x - h)) / (2 * h)
+        assert abs(float(orc.gelu_erf_grad(x)) - float(fd)) < 5e-10, x
+        fd = (orc.gelu_tanh(x + h) - orc.gelu_tanh(x - h)) / (2 * h)
+        assert abs(float(orc.gelu_tanh_grad(x)) - float(fd)) < 5e-10, x
+
+
+def test_gelu_derivative_special_values():
+    # at 0 only Phi(0) = 1/2 is left; far out the function is the identity or zero
+    assert float(orc.gelu_erf_grad(0.0)) == 0.5 and float(orc.gelu_tanh_grad(0.0)) == 0.5
+    assert abs(float(orc.gelu_erf_grad(12.0)) - 1.0) < 1e-15 and abs(float(orc.gelu_erf_grad(-12.0))) < 1e-15
+    # Phi(x) + x phi(x) at x = 1 and -1 from the tabulated Phi(1) and phi(1) = e^{-1/2}/sqrt(2 pi)
+    phi1 = np.exp(-0.5) / np.sqrt(2 * np.pi)
+    assert abs(float(orc.gelu_erf_grad(1.0)) - (0.841344746068543 + phi1)) < 1e-14
+    assert abs(float(orc.gelu_erf_grad(-1.0)) - (0.158655253931457 - phi1)) < 1e-14
+    # symmetry that follows from Phi(-x) = 1 - Phi(x): g'(x) + g'(-x) = 1
+    for x in (0.3, 1.7, 4.0):
+        assert abs(float(orc.gelu_erf_grad(x)) + float(orc.gelu_erf_grad(-x)) - 1.0) < 1e-15
+        assert abs(float(orc.gelu_tanh_grad(x)) + float(orc.gelu_tanh_grad(-x)) - 1.0) < 1e-15
+    # GELU has its minimum where the derivative changes sign: bracket it and check that
+    # the function is indeed smallest there
+    lo, hi = -1.0, -0.5
+    assert orc.gelu_erf_grad(lo) < 0 < orc.gelu_erf_grad(hi)
+    for _ in range(60):
+        mid = 0.5 * (lo + hi)
+        lo, hi = (mid, hi) if orc.gelu_erf_grad(mid) < 0 else (lo, mid)
+    xs = np.linspace(-3, 3, 6001)
+    assert abs(xs[np.argmin(orc.gelu_erf(xs))] - lo) < 2e-3
+
+
+def test_dx_with_activation_gradient():
+    q, m, kb, n = 3, 5, 4, 6
+    r = _rng(21)
+    dys = [r.standard_normal((m, n)) for _ in range(q)]
+    ws = [r.standard_normal((kb, n)) for _ in range(q)]
+    z = r.standard_normal((m, kb)) * 2
+    dx = orc.bwd_dx_panels(dys, ws)
+    # identity activation changes nothing; GELU scales element by element
+    assert np.array_equal(orc.bwd_dx_act_panels(dys, ws, z, orc.ACT_NONE), dx)
+    got = orc.bwd_dx_act_panels(dys, ws, z, orc.ACT_GELU_ERF)
+    assert np.allclose(got, dx * orc.gelu_erf_grad(z), rtol=0, atol=1e-14)
+    rows = np.array([4, 0, 2])
+    assert np.array_equal(orc.bwd_dx_act_panels(dys, ws, z, orc.ACT_GELU_ERF, rows=rows), got[rows])
+    # chain rule end to end: loss = sum(dOut * gelu(Z)) has dL/dZ = dOut * gelu'(Z);
+    # with dOut = dX this is a directional derivative that central differences reproduce
+    e = r.standard_normal((m, kb))
+    h = 1e-6
+    fd = (np.sum(dx * orc.gelu_erf(z + h * e)) - np.sum(dx * orc.gelu_erf(z - h * e))) / (2 * h)
+    assert abs(fd - np.sum(got * e)) < 1e-7 * max(1.0, abs(fd))
+
+
+def test_bias_gradient():
+    q, m, n = 3, 4, 5
+    r = _rng(22)
+    dys = [r.standard_normal((m, n)) for _ in range(q)]
+    db = orc.bias_grad_panels(dys)
+    # brute force, one column at a time
+    for s in range(n):
+        tot = 0.0
+        for t in range(q):
+            for row in range(m):
+                tot += dys[t][row, s]
+        assert abs(db[s] - tot) < 1e-14
+    # all-ones dY counts the rows; the grand total is the sum of everything
+    ones = [np.ones((m, n)) for _ in range(q)]
+    assert np.array_equal(orc.bias_grad_panels(ones), np.full(n, float(q * m)))
+    assert abs(db.sum() - sum(p.sum() for p in dys)) < 1e-13
+    # depth layers add up
+    acc = np.zeros(n)
+    orc.bias_grad_panels(dys, accumulate_into=acc)
+    orc.bias_grad_panels(ones, accumulate_into=acc)
+    assert np.allclose(acc, db + q * m, rtol=0, atol=1e-14)
+    # it is the gradient of the bias: <db, e> equals the change of sum(dY * (Z + e)) along e,
+    # which does not depend on Z
+    e = r.standard_normal(n)
+    assert abs(sum((p * e[None, :]).sum() for p in dys) - db @ e) < 1e-13
+
+
+def test_bias_gradient_of_the_full_grid_is_the_column_sum_of_dy():
+    """Row 0 of the grid ends up with the column sums of the unpartitioned dY, slice j:
+    for every depth layer k the q panels are block rows t + k q of block column j."""
+    q, d, m, n = 2, 2, 3, 4
+    a, c = m * q * d, n * q
+    dY = _rng(23).standard_normal((a, c))
+    for j in range(q):
+        acc = np.zeros(n)
+        for k in range(d):
+            panels = [np.ascontiguousarray(dY[(t + k * q) * m:(t + k * q + 1) * m, j * n:(j + 1) * n])
+                      for t in range(q)]
+            orc.bias_grad_panels(panels, accumulate_into=acc)
+        assert np.allclose(acc, dY[:, j * n:(j + 1) * n].sum(axis=0), rtol=0, atol=1e-13)
