@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--all", action="store_true", help="also time every other bf16 workload")
+    ap.add_argument("--epilogues", action="store_true",
+                    help="also time dX through GELU' and dW with the bias gradient beside the plain calls")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -76,6 +78,22 @@ class LayerState:
         b = self.sets[s % len(self.sets)]
         self.tess.linear_bwd_dw(self.desc, b["xl"], b["dyl"], b["dw"], accumulate=True,
                                 workspace=self.ws)
+
+    # the backward epilogues next to the path (timed by --epilogues only)
+    def dx_act(self, s):
+        b = self.sets[s % len(self.sets)]
+        if "z" not in b:
+            import torch
+            b["z"] = torch.randn((self.L.m, self.L.kb), device="cuda:0").to(torch.bfloat16)
+        self.tess.linear_bwd_dx_act(self.desc, b["dyl"], b["wl"], b["z"], 1, b["dx"], workspace=self.ws)
+
+    def dw_bias(self, s):
+        b = self.sets[s % len(self.sets)]
+        if "db" not in b:
+            import torch
+            b["db"] = torch.zeros((self.L.n,), dtype=torch.float32, device="cuda:0")
+        self.tess.linear_bwd_dw_bias(self.desc, b["xl"], b["dyl"], b["dw"], b["db"], accumulate=True,
+                                     workspace=self.ws)
 
 
 def time_workload(torch, tess, B, wl, w, steps, warmup):
@@ -255,6 +273,29 @@ def main():
                      "flop_per_launch": dom_layer.flops_call, "avg_ms": dom["ms"],
                      "traffic": traffic},
     }
+    if args.epilogues:
+        ep = {}
+        for st in res["layers"]:
+            for plain, fused in (("dx", "dx_act"), ("dw", "dw_bias")):
+                # alternate the two variants launch by launch so that both see the same clocks
+                fp, ff = getattr(st, plain), getattr(st, fused)
+                fp(0); ff(0)
+                torch.cuda.synchronize()
+                marks = []
+                for s_ in range(args.steps):
+                    for fn in (fp, ff):
+                        e = torch.cuda.Event(enable_timing=True)
+                        e.record()
+                        marks.append(e)
+                        fn(s_)
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                marks.append(e)
+                torch.cuda.synchronize()
+                tp = sum(marks[2 * i].elapsed_time(marks[2 * i + 1]) for i in range(args.steps)) / args.steps
+                tf = sum(marks[2 * i + 1].elapsed_time(marks[2 * i + 2]) for i in range(args.steps)) / args.steps
+                ep[f"{st.L.name}.{fused}"] = {plain + "_ms": round(tp, 4), fused + "_ms": round(tf, 4)}
+        out["backward_epilogues"] = ep
     layers0 = res["layers"]
     if args.all:
         others = {}

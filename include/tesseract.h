@@ -120,8 +120,38 @@ tess_status tess_linear_bwd_dw(const tess_desc* desc,
                                void* dw_out, int64_t lddw, int accumulate,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Input gradient through the activation that produced this layer's input (the MLP's
+ * middle activation, Section 2.4): the same sum as tess_linear_bwd_dx, multiplied
+ * element by element by the derivative of `act` at the saved pre-activation,
+ *   dZ_{i,j,k} = ( sum_{t<q} dY_{i,t,k} * (W_{j,t})^T ) .* act'(Z_{i,j,k}).
+ *   preact : device, [m, kb], ldz, in in_dtype: what the previous layer's
+ *            tess_linear_fwd wrote to preact_out (its sum plus bias).
+ *   act    : TESS_ACT_NONE makes this call identical to tess_linear_bwd_dx.
+ *   dz_out : device, [m, kb], lddz, out_dtype.  Must not alias preact.           */
+tess_status tess_linear_bwd_dx_act(const tess_desc* desc,
+                                   const void* const* dy_panels, int64_t lddy,
+                                   const void* const* w_panels, int64_t ldw,
+                                   const void* preact, int64_t ldz, int act,
+                                   void* dz_out, int64_t lddz,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Weight gradient as tess_linear_bwd_dw, plus the bias gradient of the same depth
+ * layer from the dY panels the call already streams (Section 3.2, bias-add: the
+ * gradients of block column j are reduced along the column to grid row 0; the q
+ * panels dY_{t,j,k} are exactly that column's blocks):
+ *   db^(k)_j[s] = sum_{t<q} sum_{r<m} dY_{t,j,k}[r, s].
+ *   dbias_out : device, [n], always fp32; overwritten when accumulate == 0, added
+ *               to when accumulate == 1 (the depth sum, like dw_out).              */
+tess_status tess_linear_bwd_dw_bias(const tess_desc* desc,
+                                    const void* const* x_panels, int64_t ldx,
+                                    const void* const* dy_panels, int64_t lddy,
+                                    void* dw_out, int64_t lddw, void* dbias_out, int accumulate,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Bytes of device scratch that the call `op` (a tess_op) needs for this
- * descriptor on the current device (0 when none).  Pure host arithmetic. */
+ * descriptor on the current device (0 when none).  TESS_OP_BWD_DX also covers
+ * tess_linear_bwd_dx_act and TESS_OP_BWD_DW covers tess_linear_bwd_dw_bias.  Pure
+ * host arithmetic. */
 size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
 
 /* Launch shape that the call `op` would use for this descriptor when operands are

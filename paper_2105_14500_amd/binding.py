@@ -19,7 +19,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
 
 EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
-           "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate", "tess_tile_of_block", "tess_desc_check", "tess_block_shape",
+           "tess_linear_bwd_dx_act", "tess_linear_bwd_dw_bias",
+           "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate",
+           "tess_tile_of_block", "tess_desc_check", "tess_block_shape",
            "tess_status_string", "tess_version"]
 
 
@@ -57,6 +59,10 @@ def lib():
         L.tess_linear_bwd_dx.argtypes = [dp, pp, i64, pp, i64, vp, i64, vp, sz, vp]
         L.tess_linear_bwd_dw.restype = cint
         L.tess_linear_bwd_dw.argtypes = [dp, pp, i64, pp, i64, vp, i64, cint, vp, sz, vp]
+        L.tess_linear_bwd_dx_act.restype = cint
+        L.tess_linear_bwd_dx_act.argtypes = [dp, pp, i64, pp, i64, vp, i64, cint, vp, i64, vp, sz, vp]
+        L.tess_linear_bwd_dw_bias.restype = cint
+        L.tess_linear_bwd_dw_bias.argtypes = [dp, pp, i64, pp, i64, vp, i64, vp, cint, vp, sz, vp]
         L.tess_linear_workspace_bytes.restype = sz
         L.tess_linear_workspace_bytes.argtypes = [dp, cint]
         i32p = ctypes.POINTER(ctypes.c_int32)
@@ -215,6 +221,38 @@ def linear_bwd_dx(desc, dy_panels, w_panels, dx_out, workspace=None, stream=None
                                   _stream(stream))
     if st:
         raise TessError(st, "tess_linear_bwd_dx")
+
+
+def linear_bwd_dx_act(desc, dy_panels, w_panels, preact, act, dz_out, workspace=None, stream=None):
+    """tess_linear_bwd_dx_act: dz_out = (sum_t dy_panels[t] @ w_panels[t]^T) * act'(preact)."""
+    m, kb, n = block_shape(desc)
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels")
+    wp, ldw = _panel_array(w_panels, kb, n, "w_panels")
+    op, ldo = _out(dz_out, m, kb, "dz_out")
+    zp, ldz = _out(preact, m, kb, "preact") if preact is not None else (None, 0)
+    wsp, wsb = _ws(workspace)
+    st = lib().tess_linear_bwd_dx_act(ctypes.byref(desc), dyp, lddy, wp, ldw, zp, ldz, act, op, ldo,
+                                      wsp, wsb, _stream(stream))
+    if st:
+        raise TessError(st, "tess_linear_bwd_dx_act")
+
+
+def linear_bwd_dw_bias(desc, x_panels, dy_panels, dw_out, dbias_out, accumulate=False,
+                       workspace=None, stream=None):
+    """tess_linear_bwd_dw_bias: linear_bwd_dw plus dbias_out (+)= column sums of the dy panels."""
+    m, kb, n = block_shape(desc)
+    xp, ldx = _panel_array(x_panels, m, kb, "x_panels")
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels")
+    op, ldo = _out(dw_out, kb, n, "dw_out")
+    if dbias_out is not None and (dbias_out.dtype != torch.float32 or tuple(dbias_out.shape) != (n,)
+                                  or not dbias_out.is_cuda or not dbias_out.is_contiguous()):
+        raise ValueError(f"dbias_out: need a contiguous device float32 tensor of shape {(n,)}")
+    bp = ctypes.c_void_p(dbias_out.data_ptr()) if dbias_out is not None else None
+    wsp, wsb = _ws(workspace)
+    st = lib().tess_linear_bwd_dw_bias(ctypes.byref(desc), xp, ldx, dyp, lddy, op, ldo, bp,
+                                       1 if accumulate else 0, wsp, wsb, _stream(stream))
+    if st:
+        raise TessError(st, "tess_linear_bwd_dw_bias")
 
 
 def linear_bwd_dw(desc, x_panels, dy_panels, dw_out, accumulate=False, workspace=None,

@@ -60,7 +60,9 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
     if (const char* e = getenv("TESS_TILE")) { const int v = atoi(e); if (v == 128 || (v == 256 && p.direct && M >= 256 && N >= 256)) p.bm = p.bn = v; }
     const int64_t tiles2 = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
     (void)tiles;
-    if (p.splits > 1) p.ws_bytes = (size_t)p.splits * tiles2 * p.bm * p.bn * sizeof(float);
+    if (p.splits > 1)
+        p.ws_bytes = (size_t)p.splits * tiles2 * p.bm * p.bn * sizeof(float) +
+                     (((size_t)p.splits * N * sizeof(float) + 255) & ~(size_t)255);   // + column sums
     return p;
 }
 
@@ -201,10 +203,10 @@ tess_status tess_linear_fwd(const tess_desc* desc, const void* const* a_panels, 
     return run(g, workspace, workspace_bytes, hip_stream);
 }
 
-tess_status tess_linear_bwd_dx(const tess_desc* desc, const void* const* dy_panels, int64_t lddy,
-                               const void* const* w_panels, int64_t ldw, void* dx_out,
-                               int64_t lddx, void* workspace, size_t workspace_bytes,
-                               void* hip_stream)
+static tess_status bwd_dx_impl(const tess_desc* desc, const void* const* dy_panels, int64_t lddy,
+                               const void* const* w_panels, int64_t ldw, const void* preact,
+                               int64_t ldz, int act, bool with_act, void* dx_out, int64_t lddx,
+                               void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     tess_status st = check_desc(desc);
     if (st != TESS_OK) return st;
@@ -214,7 +216,16 @@ tess_status tess_linear_bwd_dx(const tess_desc* desc, const void* const* dy_pane
     const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
                   n = desc->c / desc->q;
     if (lddy < n || ldw < n || lddx < kb) return TESS_ERR_SHAPE;
+    if (with_act) {
+        if (act != TESS_ACT_NONE && act != TESS_ACT_GELU_ERF && act != TESS_ACT_GELU_TANH)
+            return TESS_ERR_UNSUPPORTED;
+        if (act != TESS_ACT_NONE) {
+            if (!preact) return TESS_ERR_NULL;
+            if (ldz < kb) return TESS_ERR_SHAPE;
+        }
+    }
     GemmArgs g{};
+    if (with_act && act != TESS_ACT_NONE) { g.zin = preact; g.ldz = ldz; g.dact = act; }
     for (int t = 0; t < desc->q; ++t) { g.a[t] = dy_panels[t]; g.b[t] = w_panels[t]; }
     g.q = desc->q; g.M = (int32_t)m; g.N = (int32_t)kb; g.Kp = (int32_t)n;
     g.lda = lddy; g.ldb = ldw; g.out = dx_out; g.ldo = lddx; g.preact = nullptr; g.bias = nullptr;
@@ -223,16 +234,35 @@ tess_status tess_linear_bwd_dx(const tess_desc* desc, const void* const* dy_pane
     return run(g, workspace, workspace_bytes, hip_stream);
 }
 
-tess_status tess_linear_bwd_dw(const tess_desc* desc, const void* const* x_panels, int64_t ldx,
+tess_status tess_linear_bwd_dx(const tess_desc* desc, const void* const* dy_panels, int64_t lddy,
+                               const void* const* w_panels, int64_t ldw, void* dx_out,
+                               int64_t lddx, void* workspace, size_t workspace_bytes,
+                               void* hip_stream)
+{
+    return bwd_dx_impl(desc, dy_panels, lddy, w_panels, ldw, nullptr, 0, TESS_ACT_NONE, false,
+                       dx_out, lddx, workspace, workspace_bytes, hip_stream);
+}
+
+tess_status tess_linear_bwd_dx_act(const tess_desc* desc, const void* const* dy_panels,
+                                   int64_t lddy, const void* const* w_panels, int64_t ldw,
+                                   const void* preact, int64_t ldz, int act, void* dz_out,
+                                   int64_t lddz, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream)
+{
+    return bwd_dx_impl(desc, dy_panels, lddy, w_panels, ldw, preact, ldz, act, true, dz_out, lddz,
+                       workspace, workspace_bytes, hip_stream);
+}
+
+static tess_status bwd_dw_impl(const tess_desc* desc, const void* const* x_panels, int64_t ldx,
                                const void* const* dy_panels, int64_t lddy, void* dw_out,
-                               int64_t lddw, int accumulate, void* workspace,
-                               size_t workspace_bytes, void* hip_stream)
+                               int64_t lddw, void* dbias_out, bool with_bias, int accumulate,
+                               void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     tess_status st = check_desc(desc);
     if (st != TESS_OK) return st;
     if ((st = check_panels(x_panels, desc->q)) != TESS_OK) return st;
     if ((st = check_panels(dy_panels, desc->q)) != TESS_OK) return st;
-    if (!dw_out) return TESS_ERR_NULL;
+    if (!dw_out || (with_bias && !dbias_out)) return TESS_ERR_NULL;
     if (accumulate != 0 && accumulate != 1) return TESS_ERR_UNSUPPORTED;
     const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
                   n = desc->c / desc->q;
@@ -244,7 +274,26 @@ tess_status tess_linear_bwd_dw(const tess_desc* desc, const void* const* x_panel
     g.act = TESS_ACT_NONE; g.out_f32 = accumulate ? 1 : (desc->out_dtype == TESS_F32);
     g.accumulate = accumulate;
     g.a_kc = 0; g.b_kc = 0; g.in_f32 = desc->in_dtype == TESS_F32;
+    g.colsum = with_bias ? static_cast<float*>(dbias_out) : nullptr;
     return run(g, workspace, workspace_bytes, hip_stream);
+}
+
+tess_status tess_linear_bwd_dw(const tess_desc* desc, const void* const* x_panels, int64_t ldx,
+                               const void* const* dy_panels, int64_t lddy, void* dw_out,
+                               int64_t lddw, int accumulate, void* workspace,
+                               size_t workspace_bytes, void* hip_stream)
+{
+    return bwd_dw_impl(desc, x_panels, ldx, dy_panels, lddy, dw_out, lddw, nullptr, false,
+                       accumulate, workspace, workspace_bytes, hip_stream);
+}
+
+tess_status tess_linear_bwd_dw_bias(const tess_desc* desc, const void* const* x_panels,
+                                    int64_t ldx, const void* const* dy_panels, int64_t lddy,
+                                    void* dw_out, int64_t lddw, void* dbias_out, int accumulate,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return bwd_dw_impl(desc, x_panels, ldx, dy_panels, lddy, dw_out, lddw, dbias_out, true,
+                       accumulate, workspace, workspace_bytes, hip_stream);
 }
 
 tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream)

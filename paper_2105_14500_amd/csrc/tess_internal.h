@@ -34,7 +34,16 @@ struct GemmArgs {
     int32_t accumulate;     // 1: out (fp32) += result
     int32_t a_kc, b_kc;     // operand orientation
     int32_t in_f32;         // 1: inputs fp32, 0: bf16
-    // split of the K loop over gridDim.z; partials go to ws in the accumulator layout
+    // optional: multiply the result by dact'(zin[row, col]) before the store (zin in the
+    // input dtype, leading dimension ldz)
+    const void* zin;
+    int64_t ldz;
+    int32_t dact;           // tess_act whose derivative is applied
+    // optional: column sums of the B operand over the whole contraction, [N] fp32,
+    // overwritten or added to according to `accumulate`
+    float* colsum;
+    // split of the K loop over gridDim.z; partials go to ws in the accumulator layout,
+    // followed by splits x N partial column sums
     int32_t splits;
     float* ws;
 };

@@ -52,6 +52,39 @@ __device__ __forceinline__ float gelu_tanh_f(float x)
     const float c = 0.79788456080286535588f;
     return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
 }
+// Derivatives: d/dx [x Phi(x)] = Phi(x) + x phi(x); for the tanh form the chain rule on
+// u = c (x + 0.044715 x^3).
+__device__ __forceinline__ float gelu_erf_grad_f(float x)
+{
+    const float Phi = 0.5f * (1.0f + erff(x * 0.70710678118654752440f));
+    return Phi + x * 0.39894228040143267794f * __expf(-0.5f * x * x);
+}
+__device__ __forceinline__ float gelu_tanh_grad_f(float x)
+{
+    const float c = 0.79788456080286535588f;
+    const float th = tanhf(c * (x + 0.044715f * x * x * x));
+    return 0.5f * (1.0f + th) + 0.5f * x * (1.0f - th * th) * c * (1.0f + 0.134145f * x * x);
+}
+// The same erfc form as gelu_erf_fast; its exponential is the normal density up to a factor.
+__device__ __forceinline__ float gelu_erf_grad_fast(float x)
+{
+    const float z = __builtin_fabsf(x) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
+    float p = __builtin_fmaf(1.061405429f, t, -1.453152027f);
+    p = __builtin_fmaf(p, t, 1.421413741f);
+    p = __builtin_fmaf(p, t, -0.284496736f);
+    p = __builtin_fmaf(p, t, 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(x * x * -0.72134752044448170368f);   // exp(-x^2/2)
+    const float erfc_z = p * t * e;
+    const float one_plus_erf = x < 0.0f ? erfc_z : 2.0f - erfc_z;
+    return __builtin_fmaf(x * 0.39894228040143267794f, e, 0.5f * one_plus_erf);
+}
+__device__ __forceinline__ float apply_act_grad(float z, int act)
+{
+    if (act == TESS_ACT_GELU_ERF) return gelu_erf_grad_f(z);
+    if (act == TESS_ACT_GELU_TANH) return gelu_tanh_grad_f(z);
+    return 1.0f;
+}
 __device__ __forceinline__ float apply_act(float z, int act)
 {
     if (act == TESS_ACT_GELU_ERF) return gelu_erf_f(z);
@@ -87,6 +120,7 @@ __device__ __forceinline__ void store_out(const GemmArgs& g, int row, int col, f
         else ((uint16_t*)g.preact)[o] = f32_to_bf16_bits(z);
     }
     float y = apply_act(z, g.act);
+    if (g.zin) y *= apply_act_grad(load_in(g.zin, (int64_t)row * g.ldz + col, g.in_f32), g.dact);
     if (g.out_f32) {
         float* op = (float*)g.out + o;
         *op = g.accumulate ? (*op + y) : y;
@@ -115,6 +149,9 @@ __global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
     // element (kk, col) of the B operand: b_kc ? [col*ldb + kk] : [kk*ldb + col]
     const int64_t b_cs = g.b_kc ? g.ldb : 1, b_ks = g.b_kc ? 1 : g.ldb;
     float acc[4][4] = {};
+    // column sums of the B operand: the first tile row, one thread per column
+    const bool cs_thread = g.colsum && blockIdx.y == 0 && tid < GT;
+    float cs = 0.0f;
     for (int t = 0; t < g.q; ++t) {
         const void* Ap = g.a[t];
         const void* Bp = g.b[t];
@@ -132,6 +169,9 @@ __global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
                                  ? load_in(Bp, kidb * b_ks + col * b_cs, g.in_f32) : 0.0f;
             }
             __syncthreads();
+            if (cs_thread) {
+                for (int kk = 0; kk < GK; ++kk) cs += Bs[kk][tid];   // rows past Kp are zero
+            }
 #pragma unroll
             for (int kk = 0; kk < GK; ++kk) {
                 float av[4], bv[4];
@@ -145,6 +185,8 @@ __global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
             __syncthreads();
         }
     }
+    if (cs_thread && col0 + tid < g.N)
+        g.colsum[col0 + tid] = g.accumulate ? g.colsum[col0 + tid] + cs : cs;
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const int row = row0 + ty * 4 + x;
@@ -388,11 +430,12 @@ __device__ __forceinline__ u32x2 pack_bf16x4(floatx4 v)
     return w;
 }
 
-enum : int { MODE_BF16 = 0, MODE_BF16_GELU = 1, MODE_F32 = 2, MODE_F32_ACC = 3, MODE_GENERIC = 4 };
+enum : int { MODE_BF16 = 0, MODE_BF16_GELU = 1, MODE_F32 = 2, MODE_F32_ACC = 3, MODE_GENERIC = 4,
+             MODE_BF16_DGELU = 5 };
 
 template <int MODE>
 __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, floatx4 v, floatx4 bias,
-                                      bool vec)
+                                      bool vec, u32x2 zbits = u32x2{0u, 0u})
 {
     const bool out_f32 = MODE == MODE_GENERIC ? (g.out_f32 != 0) : (MODE == MODE_F32 || MODE == MODE_F32_ACC);
     const bool accumulate = MODE == MODE_GENERIC ? (g.accumulate != 0) : (MODE == MODE_F32_ACC);
@@ -413,6 +456,16 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
             if (full) *(u32x2*)p = w;
             else for (int e = 0; e < nvalid; ++e) p[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
         }
+    }
+    if (MODE == MODE_BF16_DGELU) {
+        // zbits: the bf16 pre-activations of the same four columns, fetched by the caller
+        // ahead of time (elements past the edge are zero and their products are not stored)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            v[e] *= gelu_erf_grad_fast(__uint_as_float((e & 1) ? (zbits[e >> 1] & 0xffff0000u) : (zbits[e >> 1] << 16)));
+    } else if (MODE == MODE_GENERIC && g.zin) {
+        for (int e = 0; e < nvalid; ++e)
+            v[e] *= apply_act_grad(load_in(g.zin, (int64_t)row * g.ldz + col + e, g.in_f32), g.dact);
     }
     if (act != TESS_ACT_NONE) {
         if (MODE == MODE_BF16_GELU) {
@@ -440,7 +493,14 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
 }
 
 // WGM x WGN wavefronts tile the BM x BN macro tile; each owns (BM/WGM) x (BN/WGN).
-template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT>
+// COLSUM: the wavefronts in the first tile row that hold the top wave tile also sum the
+// columns of the B operand over the contraction, from the B fragments they already hold
+// in registers: four 2-element bf16 dot products with (1, 1) per fragment and k16 step,
+// fp32 accumulation, issued in the shadow of the MFMAs.  (An extra MFMA with an all-ones
+// A fragment would need accumulator registers that the tile already uses up: the
+// compiler then copies 16 registers in and out around every such MFMA.)
+template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT,
+          bool COLSUM = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
 {
     constexpr int NT = 64 * WGM * WGN;
@@ -487,6 +547,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     static_for<FM * FN>([&](auto f) {
         static_for<16>([&](auto r) { acc[f][r()] = 0.0f; });
     });
+    // column sums (COLSUM only)
+    const bool cs_wave = COLSUM && __builtin_amdgcn_readfirstlane((int)(g.colsum != nullptr && tm == 0 && wm == 0));
+    float cs[COLSUM ? FN : 1];
+    if constexpr (COLSUM) {
+        static_for<FN>([&](auto j) { cs[j] = 0.0f; });
+    }
 
     // byte advance of one stage along K for each operand
     const uint32_t a_kstep = A_KC ? (uint32_t)BK * 2 : (uint32_t)(BK * g.lda * 2);
@@ -523,6 +589,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             side(x);
             __builtin_amdgcn_sched_barrier(0);
         });
+        if constexpr (COLSUM) {
+            if (cs_wave) {
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                const bf16x2 one2 = {(__bf16)1.0f, (__bf16)1.0f};
+                static_for<FN>([&](auto j) {
+                    const bf16x8 b = bfr[buf][j];
+                    cs[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(b, b, 0, 1), one2, cs[j], false);
+                    cs[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(b, b, 2, 3), one2, cs[j], false);
+                    cs[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(b, b, 4, 5), one2, cs[j], false);
+                    cs[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(b, b, 6, 7), one2, cs[j], false);
+                });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
     constexpr int LASTBUF = (KSTEPS - 1) & 1;
     constexpr int NSLOT = KSTEPS * FM * FN;            // MFMA slots per tile
@@ -664,6 +744,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     }
 
     // ---- epilogue
+    if constexpr (COLSUM) {
+        // lane l holds column l % 32 of each fragment for the k-values 8 (l / 32) .. + 7 of
+        // every k16 step: the two halves of the wavefront add up to the column sum
+        if (cs_wave) {
+            float* part = g.ws + (size_t)g.splits * nb * (BM * BN) + (size_t)blockIdx.z * g.N;
+            static_for<FN>([&](auto j) {
+                const float v = cs[j] + __shfl_xor(cs[j], 32, 64);
+                const int col = col0 + wn * WTN + j * 32 + lane;
+                if (lane < 32 && col < g.N) {
+                    if (g.splits > 1) part[col] = v;
+                    else g.colsum[col] = g.accumulate ? g.colsum[col] + v : v;
+                }
+            });
+        }
+    }
     if (g.splits > 1) {
         // partial sums in accumulator order: [(z*nb + tile)][wave][frag][reg][lane]
         float* w = g.ws + ((size_t)blockIdx.z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
@@ -689,10 +784,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
         const int esize = g.out_f32 ? 4 : 2;
         const bool vec = ((g.ldo * esize) % 16 == 0) &&
                          ((reinterpret_cast<uintptr_t>(g.out) & 15u) == 0) &&
-                         (!g.preact || (reinterpret_cast<uintptr_t>(g.preact) & 15u) == 0);
+                         (!g.preact || (reinterpret_cast<uintptr_t>(g.preact) & 15u) == 0) &&
+                         (!g.zin || (((reinterpret_cast<uintptr_t>(g.zin) & 7u) == 0) && (g.ldz % 4 == 0)));
         // chunk c of row r is kept at chunk c ^ (8 * bit 2 of r): the two half-waves of
         // a fragment (rows r and r+4) then write to different banks
+        constexpr int NIT = HR / RPI;                  // passes of the drain loop per half
+        // dX through GELU': the pre-activations are fetched before the accumulators are staged,
+        // so that their latency is hidden behind the LDS traffic instead of sitting in the loop
+        const bool dgelu = g.zin && g.dact == TESS_ACT_GELU_ERF && !g.out_f32 && !g.in_f32 &&
+                           !g.preact && g.act == TESS_ACT_NONE;
         static_for<2>([&](auto half) {
+            const int wrow0 = row0 + wm * WTM + half * HR, wcol0 = col0 + wn * WTN;
+            // a lane serves the same four columns in every pass
+            const int c = lane % CPR, col = wcol0 + c * 4;
+            u32x2 zr[NIT];
+            if (dgelu) {
+                static_for<NIT>([&](auto it) {
+                    const int row = wrow0 + it * RPI + lane / CPR;
+                    zr[it] = u32x2{0u, 0u};
+                    if (row < g.M && col < g.N) {
+                        const uint16_t* zp = (const uint16_t*)g.zin + (int64_t)row * g.ldz + col;
+                        if (vec && col + 3 < g.N) {
+                            zr[it] = *(const u32x2*)zp;
+                        } else {
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < g.N) zr[it][e >> 1] |= (uint32_t)zp[e] << (16 * (e & 1));
+                        }
+                    }
+                });
+            }
             static_for<FM / 2>([&](auto ii) {
                 static_for<FN>([&](auto j) {
                     constexpr int f = (half * (FM / 2) + ii) * FN + j;
@@ -705,9 +825,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
                     __builtin_amdgcn_sched_barrier(0);
                 });
             });
-            const int wrow0 = row0 + wm * WTM + half * HR, wcol0 = col0 + wn * WTN;
-            // a lane serves the same four columns in every pass: fetch their bias once
-            const int c = lane % CPR, col = wcol0 + c * 4;
+            // fetch the bias of the lane's four columns once
             floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
             if (g.bias) {
 #pragma unroll
@@ -716,7 +834,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             }
             auto drain = [&](auto mode) {
 #pragma unroll 4
-                for (int it = 0; it < HR / RPI; ++it) {
+                for (int it = 0; it < NIT; ++it) {
                     const int rl = it * RPI + lane / CPR;
                     const int phys = c ^ (((rl >> 2) & 1) << 3);
                     const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
@@ -724,7 +842,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
                     if (row < g.M && col < g.N) emit4<mode>(g, row, col, v, bias4, vec);
                 }
             };
-            if (g.preact || g.act == TESS_ACT_GELU_TANH || (g.out_f32 && g.act != TESS_ACT_NONE))
+            if (dgelu) {
+                static_for<NIT>([&](auto it) {
+                    const int rl = it * RPI + lane / CPR;
+                    const int phys = c ^ (((rl >> 2) & 1) << 3);
+                    const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
+                    const int row = wrow0 + rl;
+                    if (row < g.M && col < g.N) emit4<MODE_BF16_DGELU>(g, row, col, v, bias4, vec, zr[it]);
+                });
+            }
+            else if (g.zin || g.preact || g.act == TESS_ACT_GELU_TANH || (g.out_f32 && g.act != TESS_ACT_NONE))
                 drain(std::integral_constant<int, MODE_GENERIC>{});
             else if (g.out_f32 && g.accumulate) drain(std::integral_constant<int, MODE_F32_ACC>{});
             else if (g.out_f32) drain(std::integral_constant<int, MODE_F32>{});
@@ -748,6 +875,13 @@ __global__ __launch_bounds__(256) void tess_splitk_reduce_kernel(GemmArgs g)
     const int tiles_n = (g.N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
     const int64_t nb = (int64_t)tiles_m * tiles_n;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g.colsum && gid < g.N) {
+        // partial column sums follow the tile partials, one row of N per split
+        const float* part = g.ws + (size_t)g.splits * nb * (BM * BN) + gid;
+        float cs = 0.0f;
+        for (int z = 0; z < g.splits; ++z) cs += part[(size_t)z * g.N];
+        g.colsum[gid] = g.accumulate ? g.colsum[gid] + cs : cs;
+    }
     const int64_t tile = gid / PER_TILE;
     if (tile >= nb) return;
     const int idx = (int)(gid % PER_TILE) * 4;           // position in accumulator order
@@ -777,12 +911,13 @@ __global__ __launch_bounds__(256) void tess_splitk_reduce_kernel(GemmArgs g)
     }
 }
 
-template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT>
+template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT,
+          bool COLSUM = false>
 static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
     constexpr int NT = 64 * WGM * WGN;
-    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT>;
+    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT, COLSUM>;
     static bool attr_set = false;   // per instantiation; the attribute is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -810,7 +945,10 @@ static hipError_t launch_layout(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     if (g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, false, DIRECT>(g, p, s);
     if (g.a_kc && g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, true, DIRECT>(g, p, s);
-    if (!g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT>(g, p, s);
+    if (!g.a_kc && !g.b_kc) {
+        if (g.colsum) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT, true>(g, p, s);
+        return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT>(g, p, s);
+    }
     return hipErrorInvalidValue;
 }
 

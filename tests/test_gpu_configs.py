@@ -75,6 +75,26 @@ def test_one_share_full_size(wname, lname):
     e = rel_err(dw[urows][:, c0:c0 + cw2], want)
     assert e <= 1e-3, ("dw", e)            # fp32 output: accumulation order only
 
+    # the backward epilogues next to the path, same buffers and workspace:
+    # weight gradient with the bias gradient from the dY panels it streams
+    dw2 = torch.zeros((kb, n), dtype=torch.float32, device="cuda:0")
+    db = torch.zeros((n,), dtype=torch.float32, device="cuda:0")
+    tess.linear_bwd_dw_bias(desc, list(x), list(dy), dw2, db, accumulate=True, workspace=ws)
+    # input gradient through a GELU whose pre-activation is a seeded N(0, 1.5^2) block
+    g = torch.Generator().manual_seed(99)
+    z = (torch.randn((m, kb), generator=g) * 1.5).to(torch.bfloat16)
+    dz = torch.full((m, kb), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    tess.linear_bwd_dx_act(desc, list(dy), list(wt), dev(z), B.ACT_GELU_ERF, dz, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dw2, dw)
+    want = orc.bias_grad_panels([np.ascontiguousarray(p) for p in dyw])
+    e = rel_err(db[c0:c0 + cw2], want)
+    assert e <= 1e-4, ("db", e)
+    assert not torch.isnan(dz).any()
+    want = orc.bwd_dx_act_panels(dys, wrows, f64(z[rows][:, u0:u0 + uw]), orc.ACT_GELU_ERF)
+    e = rel_err(dz[rows][:, u0:u0 + uw], want)
+    assert e <= TOL["bf16"], ("dz", e)
+
 
 def test_config1_full_grid_fp32():
     """q=2, d=1, fp32, X[256,256], W[256,1024], zero bias: all four processors, outputs
