@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--all", action="store_true", help="also time every other bf16 workload")
+    ap.add_argument("--mlp-chain", action="store_true",
+                    help="for a workload with an up and a down layer: also time the two layers as one "
+                         "dependent chain (pre-activation kept, GELU' and bias gradients fused)")
     ap.add_argument("--epilogues", action="store_true",
                     help="also time dX through GELU' and dW with the bias gradient beside the plain calls")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -273,6 +276,28 @@ def main():
                      "flop_per_launch": dom_layer.flops_call, "avg_ms": dom["ms"],
                      "traffic": traffic},
     }
+    if args.mlp_chain:
+        by_name = {L.name: L for L in w.layers}
+        if "up" not in by_name or "down" not in by_name:
+            raise SystemExit("--mlp-chain needs a workload with an 'up' and a 'down' layer")
+        from paper_2105_14500_amd.mlp import MlpShare
+        up = by_name["up"]
+        mlp = MlpShare(w.q, w.d, up.m, up.kb, up.n)
+        sup = next(st for st in res["layers"] if st.L.name == "up").sets[0]
+        sdn = next(st for st in res["layers"] if st.L.name == "down").sets[0]
+        # peers' blocks: the down layer's X panels stand for H, the up layer's dY panels for dZ1
+        fw = lambda: mlp.forward(sup["xl"], sup["wl"], sup["bias"], sdn["xl"], sdn["wl"], sdn["bias"])
+        bw = lambda: mlp.backward(sup["xl"], sup["wl"], sdn["xl"], sdn["wl"], sdn["dyl"], sup["dyl"])
+        for _ in range(args.warmup):
+            fw(); bw()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fw(); bw()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / args.steps * 1e3
+        out["mlp_chain"] = {"ms_per_step": round(ms, 4), "tflops": round(mlp.flops() / ms / 1e9, 1),
+                            "calls": "fwd(up, preact kept) fwd(down) dw_bias(down) dx_act(down) dw_bias(up) dx(up)"}
     if args.epilogues:
         ep = {}
         for st in res["layers"]:
