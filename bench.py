@@ -31,6 +31,10 @@ def parse():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--all", action="store_true", help="also time every other bf16 workload")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: one JSON line per grid of the paper's own "
+                         "experiment tables (QKV, attention output and the two MLP layers at the "
+                         "per-processor block shapes), inputs drawn on the device")
     ap.add_argument("--mlp-chain", action="store_true",
                     help="for a workload with an up and a down layer: also time the two layers as one "
                          "dependent chain (pre-activation kept, GELU' and bias gradients fused)")
@@ -45,7 +49,7 @@ def parse():
 class LayerState:
     """Device buffers of one layer of one processor's share (packed panels)."""
 
-    def __init__(self, torch, tess, B, wl, w, L, seed, sets):
+    def __init__(self, torch, tess, B, wl, w, L, seed, sets, on_device=False):
         self.L = L
         self.q, self.d = w.q, w.d
         self.desc = B.make_desc(w.q, w.d, 0, 0, 0, L.a, L.b, L.c, B.BF16, B.BF16)
@@ -54,9 +58,18 @@ class LayerState:
         self.sets = []
         self.host = None
         for s in range(sets):
-            inp = wl.share_inputs(w.q, L.m, L.kb, L.n, dtype="bf16", seed=seed + s,
-                                  bias_std=L.bias_std)
-            if s == 0:
+            if on_device:
+                # shape sweeps: same distributions, drawn by the device generator (seconds
+                # instead of minutes for the multi-GB panel sets); no host copy is kept
+                g = torch.Generator(device="cuda:0")
+                g.manual_seed(seed + s)
+                rn = lambda shape, std: (torch.randn(shape, generator=g, device="cuda:0") * std).to(torch.bfloat16)
+                inp = {"x": rn((w.q, L.m, L.kb), 1.0), "w": rn((w.q, L.kb, L.n), 0.02),
+                       "bias": rn((L.n,), L.bias_std), "dy": rn((w.q, L.m, L.n), 1.0)}
+            else:
+                inp = wl.share_inputs(w.q, L.m, L.kb, L.n, dtype="bf16", seed=seed + s,
+                                      bias_std=L.bias_std)
+            if s == 0 and not on_device:
                 self.host = inp
             dev = {k: v.to("cuda:0") for k, v in inp.items()}
             dev["y"] = torch.empty((L.m, L.n), dtype=torch.bfloat16, device="cuda:0")
@@ -99,13 +112,14 @@ class LayerState:
                                      workspace=self.ws)
 
 
-def time_workload(torch, tess, B, wl, w, steps, warmup):
+def time_workload(torch, tess, B, wl, w, steps, warmup, on_device=False):
     layers = []
     for li, L in enumerate(w.layers):
         per_set = 2 * w.q * (L.m * L.kb + L.kb * L.n + L.m * L.n) + 2 * (L.m * L.n + L.m * L.kb) \
             + 4 * L.kb * L.n
         sets = 1 if per_set >= 400e6 else max(2, int(600e6 // per_set))
-        layers.append(LayerState(torch, tess, B, wl, w, L, seed=1000 * li, sets=min(sets, 8)))
+        layers.append(LayerState(torch, tess, B, wl, w, L, seed=1000 * li, sets=min(sets, 8),
+                                 on_device=on_device))
 
     names = ("fwd", "dx", "dw")
 
@@ -226,6 +240,17 @@ def main():
         print(f"unknown bf16 workload {args.workload}", file=sys.stderr)
         sys.exit(2)
 
+    if args.sweep:
+        for ow in wl.PAPER_TABLE_WORKLOADS:
+            torch.cuda.empty_cache()
+            r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, on_device=True)
+            print(json.dumps({"workload": ow.name, "grid": [ow.q, ow.q, ow.d],
+                              "tflops": round(r["tflops"], 1), "ms_per_step": round(r["ms_per_step"], 4),
+                              "calls": {k: {"MxNxK": v["MxNxK"], "tile": v["tile"], "k_splits": v["k_splits"],
+                                            "ms": v["ms"], "tflops": v["tflops"]}
+                                        for k, v in r["calls"].items()}}), flush=True)
+            del r
+        return
     # what the matrix cores sustain on this device at its actual clock (no memory traffic)
     sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda:0")
     B.probe_mfma_rate(sink, 256, 2000)

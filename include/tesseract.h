@@ -62,7 +62,8 @@ typedef enum { TESS_F32 = 0, TESS_BF16 = 1 } tess_dtype;
  * forms are offered. */
 typedef enum { TESS_ACT_NONE = 0, TESS_ACT_GELU_ERF = 1, TESS_ACT_GELU_TANH = 2 } tess_act;
 
-typedef enum { TESS_OP_FWD = 0, TESS_OP_BWD_DX = 1, TESS_OP_BWD_DW = 2 } tess_op;
+typedef enum { TESS_OP_FWD = 0, TESS_OP_BWD_DX = 1, TESS_OP_BWD_DW = 2,
+               TESS_OP_BWD_DX_STEP = 3, TESS_OP_BWD_DW_STEP = 4 } tess_op;
 
 /* The problem as the paper states it: the grid, this processor's coordinates and
  * the GLOBAL matrix sizes (Alg. 3 inputs). */
@@ -148,10 +149,31 @@ tess_status tess_linear_bwd_dw_bias(const tess_desc* desc,
                                     void* dw_out, int64_t lddw, void* dbias_out, int accumulate,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The backward as Section 3.1 words it (C = A B^T and C = A^T B procedures): one step's
+ * partial product on the processor that holds the dY block, to be REDUCED by the caller
+ * to the block's owner (the reduction itself, a collective, is not part of this library;
+ * `accumulate` lets one GPU play all members of the reduce group into one buffer).
+ * Summed over the group, the partials equal tess_linear_bwd_dx / tess_linear_bwd_dw.
+ *
+ * Step t of the input gradient on processor (i,j,k):
+ *   P[m, kb] (+)= dY_{i,j,k} [m,n] * (W_{t,j})^T [n,kb],  reduced over j to owner (i,t,k).
+ * Step t of the weight gradient on processor (i,j,k):
+ *   P[kb, n] (+)= (X_{i,t,k})^T [kb,m] * dY_{i,j,k} [m,n], reduced over i to owner (t,j,k).
+ *   dy_block : device [m, n], lddy;  w_block : device [kb, n], ldw;  x_block : device [m, kb], ldx
+ *   partial_out : device, fp32 whatever out_dtype says; overwritten (accumulate 0) or added to (1). */
+tess_status tess_linear_bwd_dx_step(const tess_desc* desc, const void* dy_block, int64_t lddy,
+                                    const void* w_block, int64_t ldw,
+                                    void* partial_out, int64_t ldp, int accumulate,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+tess_status tess_linear_bwd_dw_step(const tess_desc* desc, const void* x_block, int64_t ldx,
+                                    const void* dy_block, int64_t lddy,
+                                    void* partial_out, int64_t ldp, int accumulate,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Bytes of device scratch that the call `op` (a tess_op) needs for this
  * descriptor on the current device (0 when none).  TESS_OP_BWD_DX also covers
- * tess_linear_bwd_dx_act and TESS_OP_BWD_DW covers tess_linear_bwd_dw_bias.  Pure
- * host arithmetic. */
+ * tess_linear_bwd_dx_act and TESS_OP_BWD_DW covers tess_linear_bwd_dw_bias; the *_STEP
+ * codes are the single-step partial products.  Pure host arithmetic. */
 size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
 
 /* Launch shape that the call `op` would use for this descriptor when operands are

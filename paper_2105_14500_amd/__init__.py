@@ -6,5 +6,5 @@ emulate a whole processor grid on one GPU.
 """
 from . import binding, partition  # noqa: F401
 from .binding import (TessDesc, TessError, linear_fwd, linear_bwd_dx, linear_bwd_dw,  # noqa: F401
-                      linear_bwd_dx_act, linear_bwd_dw_bias,
+                      linear_bwd_dx_act, linear_bwd_dw_bias, linear_bwd_dx_step, linear_bwd_dw_step,
                       workspace_bytes, plan, desc_check, block_shape, status_string, version)

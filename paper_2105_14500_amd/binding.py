@@ -12,7 +12,7 @@ import torch
 
 F32, BF16 = 0, 1
 ACT_NONE, ACT_GELU_ERF, ACT_GELU_TANH = 0, 1, 2
-OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
+OP_FWD, OP_BWD_DX, OP_BWD_DW, OP_BWD_DX_STEP, OP_BWD_DW_STEP = 0, 1, 2, 3, 4
 MAX_Q = 16
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
 
 EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
            "tess_linear_bwd_dx_act", "tess_linear_bwd_dw_bias",
+           "tess_linear_bwd_dx_step", "tess_linear_bwd_dw_step",
            "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate",
            "tess_tile_of_block", "tess_desc_check", "tess_block_shape",
            "tess_status_string", "tess_version"]
@@ -63,6 +64,9 @@ def lib():
         L.tess_linear_bwd_dx_act.argtypes = [dp, pp, i64, pp, i64, vp, i64, cint, vp, i64, vp, sz, vp]
         L.tess_linear_bwd_dw_bias.restype = cint
         L.tess_linear_bwd_dw_bias.argtypes = [dp, pp, i64, pp, i64, vp, i64, vp, cint, vp, sz, vp]
+        for name in ("tess_linear_bwd_dx_step", "tess_linear_bwd_dw_step"):
+            getattr(L, name).restype = cint
+            getattr(L, name).argtypes = [dp, vp, i64, vp, i64, vp, i64, cint, vp, sz, vp]
         L.tess_linear_workspace_bytes.restype = sz
         L.tess_linear_workspace_bytes.argtypes = [dp, cint]
         i32p = ctypes.POINTER(ctypes.c_int32)
@@ -253,6 +257,34 @@ def linear_bwd_dw_bias(desc, x_panels, dy_panels, dw_out, dbias_out, accumulate=
                                        1 if accumulate else 0, wsp, wsb, _stream(stream))
     if st:
         raise TessError(st, "tess_linear_bwd_dw_bias")
+
+
+def linear_bwd_dx_step(desc, dy_block, w_block, partial_out, accumulate=False, workspace=None,
+                       stream=None):
+    """tess_linear_bwd_dx_step: partial_out (fp32) (+)= dy_block @ w_block^T."""
+    m, kb, n = block_shape(desc)
+    ap, lda = _out(dy_block, m, n, "dy_block")
+    bp, ldb = _out(w_block, kb, n, "w_block")
+    op, ldo = _out(partial_out, m, kb, "partial_out")
+    wsp, wsb = _ws(workspace)
+    st = lib().tess_linear_bwd_dx_step(ctypes.byref(desc), ap, lda, bp, ldb, op, ldo,
+                                       1 if accumulate else 0, wsp, wsb, _stream(stream))
+    if st:
+        raise TessError(st, "tess_linear_bwd_dx_step")
+
+
+def linear_bwd_dw_step(desc, x_block, dy_block, partial_out, accumulate=False, workspace=None,
+                       stream=None):
+    """tess_linear_bwd_dw_step: partial_out (fp32) (+)= x_block^T @ dy_block."""
+    m, kb, n = block_shape(desc)
+    ap, lda = _out(x_block, m, kb, "x_block")
+    bp, ldb = _out(dy_block, m, n, "dy_block")
+    op, ldo = _out(partial_out, kb, n, "partial_out")
+    wsp, wsb = _ws(workspace)
+    st = lib().tess_linear_bwd_dw_step(ctypes.byref(desc), ap, lda, bp, ldb, op, ldo,
+                                       1 if accumulate else 0, wsp, wsb, _stream(stream))
+    if st:
+        raise TessError(st, "tess_linear_bwd_dw_step")
 
 
 def linear_bwd_dw(desc, x_panels, dy_panels, dw_out, accumulate=False, workspace=None,

@@ -155,6 +155,8 @@ size_t tess_linear_workspace_bytes(const tess_desc* desc, int op)
         case TESS_OP_FWD: return shape_plan(m, n, kb, desc->q, bf).ws_bytes;
         case TESS_OP_BWD_DX: return shape_plan(m, kb, n, desc->q, bf).ws_bytes;
         case TESS_OP_BWD_DW: return shape_plan(kb, n, m, desc->q, bf).ws_bytes;
+        case TESS_OP_BWD_DX_STEP: return shape_plan(m, kb, n, 1, bf).ws_bytes;
+        case TESS_OP_BWD_DW_STEP: return shape_plan(kb, n, m, 1, bf).ws_bytes;
         default: return 0;
     }
 }
@@ -173,6 +175,8 @@ tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int
         case TESS_OP_FWD: p = shape_plan(m, n, kb, desc->q, bf); break;
         case TESS_OP_BWD_DX: p = shape_plan(m, kb, n, desc->q, bf); break;
         case TESS_OP_BWD_DW: p = shape_plan(kb, n, m, desc->q, bf); break;
+        case TESS_OP_BWD_DX_STEP: p = shape_plan(m, kb, n, 1, bf); break;
+        case TESS_OP_BWD_DW_STEP: p = shape_plan(kb, n, m, 1, bf); break;
         default: return TESS_ERR_UNSUPPORTED;
     }
     *tile_m = p.bm; *tile_n = p.bn; *k_splits = p.splits;
@@ -294,6 +298,48 @@ tess_status tess_linear_bwd_dw_bias(const tess_desc* desc, const void* const* x_
 {
     return bwd_dw_impl(desc, x_panels, ldx, dy_panels, lddy, dw_out, lddw, dbias_out, true,
                        accumulate, workspace, workspace_bytes, hip_stream);
+}
+
+tess_status tess_linear_bwd_dx_step(const tess_desc* desc, const void* dy_block, int64_t lddy,
+                                    const void* w_block, int64_t ldw, void* partial_out,
+                                    int64_t ldp, int accumulate, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream)
+{
+    tess_status st = check_desc(desc);
+    if (st != TESS_OK) return st;
+    if (!dy_block || !w_block || !partial_out) return TESS_ERR_NULL;
+    if (accumulate != 0 && accumulate != 1) return TESS_ERR_UNSUPPORTED;
+    const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
+                  n = desc->c / desc->q;
+    if (lddy < n || ldw < n || ldp < kb) return TESS_ERR_SHAPE;
+    GemmArgs g{};
+    g.a[0] = dy_block; g.b[0] = w_block;
+    g.q = 1; g.M = (int32_t)m; g.N = (int32_t)kb; g.Kp = (int32_t)n;
+    g.lda = lddy; g.ldb = ldw; g.out = partial_out; g.ldo = ldp;
+    g.act = TESS_ACT_NONE; g.out_f32 = 1; g.accumulate = accumulate;
+    g.a_kc = 1; g.b_kc = 1; g.in_f32 = desc->in_dtype == TESS_F32;
+    return run(g, workspace, workspace_bytes, hip_stream);
+}
+
+tess_status tess_linear_bwd_dw_step(const tess_desc* desc, const void* x_block, int64_t ldx,
+                                    const void* dy_block, int64_t lddy, void* partial_out,
+                                    int64_t ldp, int accumulate, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream)
+{
+    tess_status st = check_desc(desc);
+    if (st != TESS_OK) return st;
+    if (!x_block || !dy_block || !partial_out) return TESS_ERR_NULL;
+    if (accumulate != 0 && accumulate != 1) return TESS_ERR_UNSUPPORTED;
+    const int64_t m = desc->a / ((int64_t)desc->q * desc->d), kb = desc->b / desc->q,
+                  n = desc->c / desc->q;
+    if (ldx < kb || lddy < n || ldp < n) return TESS_ERR_SHAPE;
+    GemmArgs g{};
+    g.a[0] = x_block; g.b[0] = dy_block;
+    g.q = 1; g.M = (int32_t)kb; g.N = (int32_t)n; g.Kp = (int32_t)m;
+    g.lda = ldx; g.ldb = lddy; g.out = partial_out; g.ldo = ldp;
+    g.act = TESS_ACT_NONE; g.out_f32 = 1; g.accumulate = accumulate;
+    g.a_kc = 0; g.b_kc = 0; g.in_f32 = desc->in_dtype == TESS_F32;
+    return run(g, workspace, workspace_bytes, hip_stream);
 }
 
 tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream)

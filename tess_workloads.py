@@ -59,6 +59,37 @@ WORKLOADS = [
 ]
 
 
+# The grids and Transformer sizes of the paper's own experiments (Tables 1 and 2: GPU shape,
+# batch size, hidden size), turned into per-processor block shapes.  The paper gives no
+# sequence length: SEQ_LEN is this build's choice.  Table 2's batch sizes give b/(dq) = 48
+# sequences per processor (its text says 24; the table is followed).  Four linear layers per
+# Transformer layer (Section 3.2): QKV h -> 3h, attention output h -> h, MLP h -> 4h -> h.
+SEQ_LEN = 512
+PAPER_TABLE_GRIDS = [
+    # (table, q, d, batch, hidden)
+    ("strong", 2, 1, 12, 3072), ("strong", 2, 2, 12, 3072), ("strong", 4, 1, 12, 3072),
+    ("strong", 4, 2, 12, 3072), ("strong", 4, 4, 16, 3072), ("strong", 8, 1, 12, 3072),
+    ("weak", 1, 1, 48, 1024), ("weak", 2, 1, 96, 2048), ("weak", 2, 2, 192, 2048),
+    ("weak", 4, 1, 192, 4096), ("weak", 4, 2, 384, 4096), ("weak", 4, 4, 768, 4096),
+    ("weak", 8, 1, 384, 8192),
+]
+
+
+def _transformer_layers(q, d, batch, h):
+    a = batch * SEQ_LEN
+    spec = [("qkv", h, 3 * h, "none", 0.02), ("out", h, h, "none", 0.02),
+            ("up", h, 4 * h, "gelu_erf", 0.02), ("down", 4 * h, h, "none", 0.02)]
+    return [Layer(name, a, b, c, a // (q * d), b // q, c // q, act, bstd)
+            for name, b, c, act, bstd in spec]
+
+
+PAPER_TABLE_WORKLOADS = [
+    Workload(f"{table}_q{q}d{d}_b{batch}_h{h}", q, d, "bf16", "one_share",
+             _transformer_layers(q, d, batch, h))
+    for table, q, d, batch, h in PAPER_TABLE_GRIDS
+]
+
+
 def torch_dtype(name: str) -> torch.dtype:
     return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
 
@@ -121,7 +152,7 @@ def share_inputs(q, m, kb, n, dtype="bf16", seed=0, bias_std=0.02, w_std=0.02, i
 
 
 def workload_by_name(name: str) -> Optional[Workload]:
-    for w in WORKLOADS:
+    for w in WORKLOADS + PAPER_TABLE_WORKLOADS:
         if w.name == name:
             return w
     return None

@@ -138,3 +138,34 @@ def test_new_entry_points_reject_bad_arguments():
     assert e.value.status == 1
     torch.cuda.synchronize()
     assert torch.all(dz == 7.0) and torch.all(dw == 7.0)
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 128, 128, 64), (3, 1, 264, 200, 136), (2, 1, 512, 256, 2048),
+                                   (2, 1, 4096, 128, 128), (2, 1, 50, 36, 28)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_stepwise_partial_products(shape, dtype):
+    """Section 3.1's own wording of the backward: one step's partial product on single blocks,
+    fp32 out, against the plain block products; accumulated over the q members of the reduce
+    group it reproduces the owner-computes calls."""
+    q, d, m, kb, n = shape
+    inp = wl.share_inputs(q, m, kb, n, dtype=dtype, seed=51, w_std=0.1)
+    desc = share_desc(q, d, m, kb, n, dtype, "f32")
+    xd, wd, dyd = dev(inp["x"]), dev(inp["w"]), dev(inp["dy"])
+    # one step each
+    p = torch.full((m, kb), float("nan"), device="cuda:0")
+    tess.linear_bwd_dx_step(desc, dyd[0], wd[0], p, workspace=workspace(desc, B.OP_BWD_DX_STEP))
+    pw = torch.full((kb, n), float("nan"), device="cuda:0")
+    tess.linear_bwd_dw_step(desc, xd[0], dyd[0], pw, workspace=workspace(desc, B.OP_BWD_DW_STEP))
+    torch.cuda.synchronize()
+    assert rel_err(p, orc.matmul_nt(f64(inp["dy"][0]), f64(inp["w"][0]))) <= 1e-5
+    assert rel_err(pw, orc.matmul_tn(f64(inp["x"][0]), f64(inp["dy"][0]))) <= 1e-5
+    # the reduce group played on one GPU: partials of members 1..q-1 added to member 0's
+    for t in range(1, q):
+        tess.linear_bwd_dx_step(desc, dyd[t], wd[t], p, accumulate=True,
+                                workspace=workspace(desc, B.OP_BWD_DX_STEP))
+        tess.linear_bwd_dw_step(desc, xd[t], dyd[t], pw, accumulate=True,
+                                workspace=workspace(desc, B.OP_BWD_DW_STEP))
+    torch.cuda.synchronize()
+    dys = [f64(inp["dy"][t]) for t in range(q)]
+    assert rel_err(p, orc.bwd_dx_panels(dys, [f64(inp["w"][t]) for t in range(q)])) <= 1e-5
+    assert rel_err(pw, orc.bwd_dw_panels([f64(inp["x"][t]) for t in range(q)], dys)) <= 1e-5

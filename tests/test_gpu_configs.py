@@ -19,6 +19,15 @@ pytestmark = pytest.mark.gpu
 
 ACT = {"none": (B.ACT_NONE, orc.ACT_NONE), "gelu_erf": (B.ACT_GELU_ERF, orc.ACT_GELU_ERF)}
 CASES = [(w.name, L.name) for w in wl.WORKLOADS if w.mode == "one_share" for L in w.layers]
+# block shapes of the paper's own experiment grids (Tables 1 and 2): three strong-scaling
+# grids with all four layers, the single-processor grid (q = 1: one panel per operand) and
+# one weak-scaling grid
+_PAPER = {"strong_q2d2_b12_h3072": ("qkv", "out", "up", "down"),
+          "strong_q4d4_b16_h3072": ("qkv", "out", "up", "down"),
+          "strong_q8d1_b12_h3072": ("qkv", "out", "up", "down"),
+          "weak_q1d1_b48_h1024": ("out", "up"),
+          "weak_q4d2_b384_h4096": ("qkv",)}
+CASES += [(name, lname) for name, lnames in _PAPER.items() for lname in lnames]
 
 
 def _sample(n, count, seed):

@@ -466,3 +466,37 @@ def test_bias_gradient_of_the_full_grid_is_the_column_sum_of_dy():
                       for t in range(q)]
             orc.bias_grad_panels(panels, accumulate_into=acc)
         assert np.allclose(acc, dY[:, j * n:(j + 1) * n].sum(axis=0), rtol=0, atol=1e-13)
+
+
+# --------------------------------------- the backward as Section 3.1 words it, step by step
+@pytest.mark.parametrize("q,d", [(2, 1), (2, 2), (3, 2)])
+def test_stepwise_partials_reduce_to_the_owner_computes_sums(q, d):
+    """Processor (i,j,k) multiplies ITS dY block by the block it receives at step t and the
+    partials are reduced along the grid row (input gradient, owner (i,t,k)) or the grid column
+    (weight gradient, owner (t,j,k)).  Written with the plain products on blocks of the global
+    matrices, both reductions must give the blocks of dY W^T and, summed over depth, X^T dY."""
+    a, b, c, m, kb, n = _sizes(q, d, 50 + q * 7 + d)
+    r = _rng(60 + q + d)
+    X, W, dY = r.standard_normal((a, b)), r.standard_normal((b, c)), r.standard_normal((a, c))
+    dX_full, dW_full = dY @ W.T, X.T @ dY
+    blkA = lambda M_, h, col, w_: np.ascontiguousarray(M_[h * m:(h + 1) * m, col * w_:(col + 1) * w_])
+    blkW = lambda u, v: np.ascontiguousarray(W[u * kb:(u + 1) * kb, v * n:(v + 1) * n])
+    dW_acc = np.zeros((b, c))
+    for k in range(d):
+        for i in range(q):
+            h = orc.block_row(q, i, k)
+            for t in range(q):
+                # input gradient of block (h, t): sum over the row's processors j
+                part = sum(orc.matmul_nt(blkA(dY, h, j, n), blkW(t, j)) for j in range(q))
+                assert np.allclose(part, dX_full[h * m:(h + 1) * m, t * kb:(t + 1) * kb], atol=1e-12)
+                # the same block from the owner-computes formula
+                own = orc.tess_bwd_dx(q, d, i, t, k, dY, W)
+                assert np.allclose(part, own, atol=1e-12)
+        for j in range(q):
+            for t in range(q):
+                # weight gradient of block (t, j), depth layer k: sum over the column's processors i
+                part = sum(orc.matmul_tn(blkA(X, orc.block_row(q, i, k), t, kb),
+                                         blkA(dY, orc.block_row(q, i, k), j, n)) for i in range(q))
+                dW_acc[t * kb:(t + 1) * kb, j * n:(j + 1) * n] += part
+                assert np.allclose(part, orc.tess_bwd_dw(q, d, t, j, k, X, dY), atol=1e-12)
+    assert np.allclose(dW_acc, dW_full, atol=1e-11)
