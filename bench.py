@@ -197,7 +197,7 @@ def cpu_baseline(torch, w, layer_state, budget_s=24.0):
         fl = 2.0 * q * L.kb * L.n * (rows_fwd + rows_dx) + 2.0 * q * L.m * cols * rows_dw
         return fl, dt
 
-    fl, dt = run(8, 8, 8)                      # calibration
+    fl, dt = run(64, 64, 64)                   # calibration (every thread gets rows)
     rate = fl / dt
     per_row = 2.0 * q * L.kb * L.n
     rows = int(max(8, min(L.m, budget_s / 3 * rate / per_row)))

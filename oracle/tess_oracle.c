@@ -319,6 +319,41 @@ void orc_bwd_dw_panels(int q, int64_t m, int64_t kb, int64_t n,
     }
 }
 
+/* ---- layer normalisation, local parts (Section 3.2, "Other procedure") -----
+ * The hidden dimension of a row is spread over the q processors of a grid row.
+ * Each computes the sum and the sum of squares of its own [m, w] block per row;
+ * the two numbers are then summed over the grid row (an all-reduce that is the
+ * caller's business; `accumulate` adds a further block's sums) and every
+ * processor normalises its block with
+ *   E[X] = S1 / n,  Var[X] = S2 / n - E[X]^2,  xhat = (x - E[X]) / sqrt(Var[X] + eps),
+ * n the full hidden size.                                                     */
+void orc_row_sums(const double* x, int64_t m, int64_t w, int64_t ldx, int accumulate,
+                  double* sums_out /* [m, 2] */)
+{
+    for (int64_t r = 0; r < m; ++r) {
+        double s1 = 0.0, s2 = 0.0;
+        for (int64_t u = 0; u < w; ++u) {
+            const double v = x[r * ldx + u];
+            s1 += v;
+            s2 += v * v;
+        }
+        sums_out[2 * r] = accumulate ? sums_out[2 * r] + s1 : s1;
+        sums_out[2 * r + 1] = accumulate ? sums_out[2 * r + 1] + s2 : s2;
+    }
+}
+
+void orc_layernorm_from_sums(const double* x, int64_t m, int64_t w, int64_t ldx,
+                             const double* sums /* [m, 2] */, int64_t n_total, double eps,
+                             double* xhat_out /* [m, w] packed */)
+{
+    for (int64_t r = 0; r < m; ++r) {
+        const double mean = sums[2 * r] / (double)n_total;
+        const double var = sums[2 * r + 1] / (double)n_total - mean * mean;
+        const double rstd = 1.0 / sqrt(var + eps);
+        for (int64_t u = 0; u < w; ++u) xhat_out[r * w + u] = (x[r * ldx + u] - mean) * rstd;
+    }
+}
+
 /* ---- per-processor formulas on the unpartitioned matrices ----------------
  * These cut the blocks out of the global matrices exactly as Alg. 3 lays
  * them out and hand them to the panel formulas above.                       */

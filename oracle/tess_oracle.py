@@ -57,6 +57,10 @@ def lib():
         L.orc_bwd_dx_act_panels.restype = None
         L.orc_bias_grad_panels.argtypes = [ctypes.c_int, i64, i64, pp, i64, ctypes.c_int, dp]
         L.orc_bias_grad_panels.restype = None
+        L.orc_row_sums.argtypes = [dp, i64, i64, i64, ctypes.c_int, dp]
+        L.orc_row_sums.restype = None
+        L.orc_layernorm_from_sums.argtypes = [dp, i64, i64, i64, dp, i64, ctypes.c_double, dp]
+        L.orc_layernorm_from_sums.restype = None
         L.orc_tess_fwd.argtypes = [ctypes.c_int] * 5 + [i64] * 3 + [dp, dp, dp, ctypes.c_int,
                                                                    dp, dp]
         L.orc_tess_fwd.restype = ctypes.c_int
@@ -238,6 +242,31 @@ def bias_grad_panels(dy_panels, accumulate_into=None):
         acc = 0
     lib().orc_bias_grad_panels(q, m, n, dyp, lddy, acc, _p(db))
     return db
+
+
+def row_sums(x, accumulate_into=None):
+    """[m, 2]: per row the sum and the sum of squares of the block x [m, w]."""
+    x = _f64(x)
+    m, w = x.shape
+    if accumulate_into is not None:
+        out = accumulate_into
+        assert out.dtype == np.float64 and out.shape == (m, 2) and out.flags.c_contiguous
+        acc = 1
+    else:
+        out = np.empty((m, 2))
+        acc = 0
+    lib().orc_row_sums(_p(x), m, w, w, acc, _p(out))
+    return out
+
+
+def layernorm_from_sums(x, sums, n_total, eps):
+    x = _f64(x)
+    sums = _f64(sums)
+    m, w = x.shape
+    assert sums.shape == (m, 2)
+    out = np.empty((m, w))
+    lib().orc_layernorm_from_sums(_p(x), m, w, w, _p(sums), n_total, float(eps), _p(out))
+    return out
 
 
 def bwd_dw_panels(x_panels, dy_panels, rows=None, accumulate_into=None):

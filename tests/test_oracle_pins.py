@@ -500,3 +500,38 @@ def test_stepwise_partials_reduce_to_the_owner_computes_sums(q, d):
                 dW_acc[t * kb:(t + 1) * kb, j * n:(j + 1) * n] += part
                 assert np.allclose(part, orc.tess_bwd_dw(q, d, t, j, k, X, dY), atol=1e-12)
     assert np.allclose(dW_acc, dW_full, atol=1e-11)
+
+
+# ----------------------------------------------- layer normalisation, local partial sums
+def test_row_sums_and_layernorm_against_numpy():
+    """Sums of q column blocks add up to the sums of the whole row, and normalising each block
+    with the summed numbers is numpy's (x - mean) / sqrt(var + eps) on the whole row."""
+    q, m, w = 3, 5, 4
+    r = _rng(70)
+    X = r.standard_normal((m, q * w)) * 3 + 1.5
+    acc = np.zeros((m, 2))
+    for j in range(q):
+        orc.row_sums(np.ascontiguousarray(X[:, j * w:(j + 1) * w]), accumulate_into=acc)
+    assert np.allclose(acc[:, 0], X.sum(axis=1), atol=1e-12)
+    assert np.allclose(acc[:, 1], (X * X).sum(axis=1), atol=1e-11)
+    one = orc.row_sums(np.ascontiguousarray(X[:, :w]))
+    assert np.allclose(one[:, 0], X[:, :w].sum(axis=1), atol=1e-12)
+    eps = 1e-5
+    want = (X - X.mean(axis=1, keepdims=True)) / np.sqrt(X.var(axis=1, keepdims=True) + eps)
+    for j in range(q):
+        got = orc.layernorm_from_sums(np.ascontiguousarray(X[:, j * w:(j + 1) * w]), acc, q * w, eps)
+        assert np.allclose(got, want[:, j * w:(j + 1) * w], atol=1e-12)
+    # rows of the result have mean 0 and variance var / (var + eps)
+    full = np.concatenate([orc.layernorm_from_sums(np.ascontiguousarray(X[:, j * w:(j + 1) * w]), acc,
+                                                   q * w, eps) for j in range(q)], axis=1)
+    assert np.allclose(full.mean(axis=1), 0.0, atol=1e-13)
+    v = X.var(axis=1)
+    assert np.allclose(full.var(axis=1), v / (v + eps), atol=1e-12)
+    # a constant row has no variance: everything is (x - x) / sqrt(eps) = 0
+    C = np.full((2, w), 7.0)
+    assert np.array_equal(orc.layernorm_from_sums(C, orc.row_sums(C), w, eps), np.zeros((2, w)))
+    # hand-computed: row (1, 2, 3, 6): sum 12, squares 50, mean 3, variance 50/4 - 9 = 3.5
+    s = orc.row_sums(np.array([[1.0, 2.0, 3.0, 6.0]]))
+    assert s.tolist() == [[12.0, 50.0]]
+    got = orc.layernorm_from_sums(np.array([[1.0, 2.0, 3.0, 6.0]]), s, 4, 0.0)
+    assert np.allclose(got, np.array([[-2.0, -1.0, 0.0, 3.0]]) / np.sqrt(3.5), atol=1e-15)
