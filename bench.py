@@ -35,6 +35,9 @@ def parse():
                     help="instead of the benchmark line: one JSON line per grid of the paper's own "
                          "experiment tables (QKV, attention output and the two MLP layers at the "
                          "per-processor block shapes), inputs drawn on the device")
+    ap.add_argument("--layernorm", action="store_true",
+                    help="instead of the benchmark line: time the local layer-normalisation kernels "
+                         "(row sums, normalise) on the workload's first layer's X block, in GB/s")
     ap.add_argument("--mlp-chain", action="store_true",
                     help="for a workload with an up and a down layer: also time the two layers as one "
                          "dependent chain (pre-activation kept, GELU' and bias gradients fused)")
@@ -240,6 +243,34 @@ def main():
         print(f"unknown bf16 workload {args.workload}", file=sys.stderr)
         sys.exit(2)
 
+    if args.layernorm:
+        L = w.layers[0]
+        # rotate over enough blocks that the working set exceeds the 256 MiB last-level cache
+        nbuf = max(2, int(1.2e9 // (L.m * L.kb * 4)))
+        xs = [torch.randn((L.m, L.kb), device="cuda:0").to(torch.bfloat16) for _ in range(nbuf)]
+        outs = [torch.empty_like(xs[0]) for _ in range(nbuf)]
+        x = xs[0]
+        sums = torch.empty((L.m, 2), dtype=torch.float32, device="cuda:0")
+        res = {}
+        for name, fn, nbytes in (("row_sums", lambda i: B.layernorm_row_sums(xs[i % nbuf], sums),
+                                  x.numel() * 2 + L.m * 8),
+                                 ("normalize", lambda i: B.layernorm_normalize(xs[i % nbuf], sums, L.kb * w.q,
+                                                                               1e-5, outs[i % nbuf]),
+                                  x.numel() * 4 + L.m * 8)):
+            for i in range(args.warmup):
+                fn(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(args.steps):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            res[name] = {"ms": round(ms, 4), "GBps": round(nbytes / ms / 1e6, 1),
+                         "frac_of_8TBps": round(nbytes / ms / 1e6 / 8000.0, 3), "bytes": nbytes}
+        print(json.dumps({"layernorm": res, "block": [L.m, L.kb], "dtype": "bf16", "workload": w.name}))
+        return
     if args.sweep:
         for ow in wl.PAPER_TABLE_WORKLOADS:
             torch.cuda.empty_cache()

@@ -170,6 +170,21 @@ tess_status tess_linear_bwd_dw_step(const tess_desc* desc, const void* x_block, 
                                     void* partial_out, int64_t ldp, int accumulate,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Layer normalisation of a hidden dimension spread over the q processors of a grid row
+ * (Section 3.2, "Other procedure": every processor computes the sums of X and X^2 of its
+ * block, the sums are all-reduced along the row, then E[X] = S1/n, Var[X] = S2/n - E[X]^2).
+ * The all-reduce is the caller's; `accumulate` adds a further block's sums so that one GPU
+ * can play the whole row.
+ *   x        : device, [m, w] in `dtype` (a tess_dtype), ldx
+ *   sums_out : device, [m, 2] fp32 packed: sum, sum of squares                      */
+tess_status tess_layernorm_row_sums(const void* x, int64_t m, int64_t w, int64_t ldx, int dtype,
+                                    void* sums_out, int accumulate, void* hip_stream);
+/* xhat = (x - S1/n) / sqrt(S2/n - (S1/n)^2 + eps) with the REDUCED sums of the whole row,
+ * n_total the full hidden size.  xhat_out: device, [m, w] in `dtype`, ldo; may equal x. */
+tess_status tess_layernorm_normalize(const void* x, int64_t m, int64_t w, int64_t ldx, int dtype,
+                                     const void* sums, int64_t n_total, float eps,
+                                     void* xhat_out, int64_t ldo, void* hip_stream);
+
 /* Bytes of device scratch that the call `op` (a tess_op) needs for this
  * descriptor on the current device (0 when none).  TESS_OP_BWD_DX also covers
  * tess_linear_bwd_dx_act and TESS_OP_BWD_DW covers tess_linear_bwd_dw_bias; the *_STEP

@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
 EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
            "tess_linear_bwd_dx_act", "tess_linear_bwd_dw_bias",
            "tess_linear_bwd_dx_step", "tess_linear_bwd_dw_step",
+           "tess_layernorm_row_sums", "tess_layernorm_normalize",
            "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate",
            "tess_tile_of_block", "tess_desc_check", "tess_block_shape",
            "tess_status_string", "tess_version"]
@@ -67,6 +68,10 @@ def lib():
         for name in ("tess_linear_bwd_dx_step", "tess_linear_bwd_dw_step"):
             getattr(L, name).restype = cint
             getattr(L, name).argtypes = [dp, vp, i64, vp, i64, vp, i64, cint, vp, sz, vp]
+        L.tess_layernorm_row_sums.restype = cint
+        L.tess_layernorm_row_sums.argtypes = [vp, i64, i64, i64, cint, vp, cint, vp]
+        L.tess_layernorm_normalize.restype = cint
+        L.tess_layernorm_normalize.argtypes = [vp, i64, i64, i64, cint, vp, i64, ctypes.c_float, vp, i64, vp]
         L.tess_linear_workspace_bytes.restype = sz
         L.tess_linear_workspace_bytes.argtypes = [dp, cint]
         i32p = ctypes.POINTER(ctypes.c_int32)
@@ -154,6 +159,35 @@ def probe_mfma_rate(sink, workgroups, iters, stream=None):
     if st:
         raise TessError(st, "tess_probe_mfma_rate")
     return workgroups * 4 * iters * 8 * 32768.0
+
+
+def layernorm_row_sums(x, sums_out, accumulate=False, stream=None):
+    """tess_layernorm_row_sums: sums_out[m, 2] (+)= per-row sum and sum of squares of x[m, w]."""
+    m, w = x.shape
+    xp, ldx = _out(x, m, w, "x")
+    if sums_out.dtype != torch.float32 or tuple(sums_out.shape) != (m, 2) or not sums_out.is_contiguous():
+        raise ValueError("sums_out: need a contiguous device float32 tensor of shape (m, 2)")
+    st = lib().tess_layernorm_row_sums(xp, m, w, ldx, dtype_code(x.dtype),
+                                       ctypes.c_void_p(sums_out.data_ptr()), 1 if accumulate else 0,
+                                       _stream(stream))
+    if st:
+        raise TessError(st, "tess_layernorm_row_sums")
+
+
+def layernorm_normalize(x, sums, n_total, eps, xhat_out, stream=None):
+    """tess_layernorm_normalize: xhat_out = (x - mean) / sqrt(var + eps) from the reduced sums."""
+    m, w = x.shape
+    xp, ldx = _out(x, m, w, "x")
+    op, ldo = _out(xhat_out, m, w, "xhat_out")
+    if xhat_out.dtype != x.dtype:
+        raise ValueError("xhat_out: same dtype as x")
+    if sums.dtype != torch.float32 or tuple(sums.shape) != (m, 2) or not sums.is_contiguous():
+        raise ValueError("sums: need a contiguous device float32 tensor of shape (m, 2)")
+    st = lib().tess_layernorm_normalize(xp, m, w, ldx, dtype_code(x.dtype),
+                                        ctypes.c_void_p(sums.data_ptr()), n_total, float(eps), op, ldo,
+                                        _stream(stream))
+    if st:
+        raise TessError(st, "tess_layernorm_normalize")
 
 
 def _panel_array(panels, rows, cols, what):

@@ -6,7 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtesseract_hip.so")
-SOURCES = [os.path.join(CSRC, "tess_api.cpp"), os.path.join(CSRC, "tess_kernels.hip")]
+SOURCES = [os.path.join(CSRC, "tess_api.cpp"), os.path.join(CSRC, "tess_kernels.hip"),
+           os.path.join(CSRC, "tess_layernorm.hip")]
 HEADERS = [os.path.join(CSRC, "tess_internal.h"), os.path.join(ROOT, "include", "tesseract.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

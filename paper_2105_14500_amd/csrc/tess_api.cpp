@@ -342,6 +342,31 @@ tess_status tess_linear_bwd_dw_step(const tess_desc* desc, const void* x_block, 
     return run(g, workspace, workspace_bytes, hip_stream);
 }
 
+tess_status tess_layernorm_row_sums(const void* x, int64_t m, int64_t w, int64_t ldx, int dtype,
+                                    void* sums_out, int accumulate, void* hip_stream)
+{
+    if (!x || !sums_out) return TESS_ERR_NULL;
+    if (m < 1 || w < 1 || ldx < w || m > ((int64_t)1 << 32)) return TESS_ERR_SHAPE;
+    if ((dtype != TESS_F32 && dtype != TESS_BF16) || (accumulate != 0 && accumulate != 1))
+        return TESS_ERR_UNSUPPORTED;
+    hipError_t e = launch_row_sums(x, m, w, ldx, dtype == TESS_F32, accumulate,
+                                   static_cast<float*>(sums_out), static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
+}
+
+tess_status tess_layernorm_normalize(const void* x, int64_t m, int64_t w, int64_t ldx, int dtype,
+                                     const void* sums, int64_t n_total, float eps, void* xhat_out,
+                                     int64_t ldo, void* hip_stream)
+{
+    if (!x || !sums || !xhat_out) return TESS_ERR_NULL;
+    if (m < 1 || w < 1 || ldx < w || ldo < w || n_total < w || m > ((int64_t)1 << 32)) return TESS_ERR_SHAPE;
+    if ((dtype != TESS_F32 && dtype != TESS_BF16) || !(eps >= 0.0f)) return TESS_ERR_UNSUPPORTED;
+    hipError_t e = launch_normalize(x, m, w, ldx, dtype == TESS_F32, static_cast<const float*>(sums),
+                                    1.0f / (float)n_total, eps, xhat_out, ldo,
+                                    static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
+}
+
 tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream)
 {
     if (!sink) return TESS_ERR_NULL;

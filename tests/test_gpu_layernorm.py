@@ -1,0 +1,52 @@
+"""GPU parity of the local layer-normalisation parts (Section 3.2, "Other procedure"): per-row
+sum and sum of squares of one processor's block, accumulated over the q blocks of a grid row
+on one GPU, and the normalisation from the reduced sums; against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2105_14500_amd import binding as B
+from oracle import tess_oracle as orc
+from gpu_util import TOL, f64, dev, rel_err, tdtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("q,m,w", [(1, 7, 33), (2, 5, 8), (4, 256, 1024), (3, 130, 72), (8, 1024, 1536)])
+def test_row_sums_and_normalize(dtype, q, m, w):
+    g = torch.Generator().manual_seed(5 + q + m)
+    X = (torch.randn((m, q * w), generator=g) * 3 + 1.5).to(tdtype(dtype))     # the whole rows
+    Xd = dev(X)
+    sums = torch.full((m, 2), float("nan"), device="cuda:0")
+    for j in range(q):                                   # strided column blocks, ld = q*w
+        B.layernorm_row_sums(Xd[:, j * w:(j + 1) * w], sums, accumulate=(j > 0))
+    eps = 1e-5
+    out = torch.full((m, q * w), float("nan"), dtype=tdtype(dtype), device="cuda:0")
+    for j in range(q):
+        B.layernorm_normalize(Xd[:, j * w:(j + 1) * w], sums, q * w, eps, out[:, j * w:(j + 1) * w])
+    torch.cuda.synchronize()
+    X64 = f64(X)
+    want_s = np.zeros((m, 2))
+    for j in range(q):
+        orc.row_sums(np.ascontiguousarray(X64[:, j * w:(j + 1) * w]), accumulate_into=want_s)
+    assert rel_err(sums, want_s) <= 1e-5
+    want = np.concatenate([orc.layernorm_from_sums(np.ascontiguousarray(X64[:, j * w:(j + 1) * w]),
+                                                   want_s, q * w, eps) for j in range(q)], axis=1)
+    assert rel_err(out, want) <= (TOL["bf16"] if dtype == "bf16" else 1e-5)
+    assert not torch.isnan(out).any()
+
+
+def test_row_sums_of_integers_are_exact_and_errors_are_reported():
+    m, w = 64, 520
+    r = np.random.default_rng(3)
+    X = torch.tensor(r.integers(-3, 4, size=(m, w)).astype(np.float32)).to(torch.bfloat16)
+    sums = torch.empty((m, 2), device="cuda:0")
+    B.layernorm_row_sums(dev(X), sums)
+    torch.cuda.synchronize()
+    assert np.array_equal(f64(sums), orc.row_sums(f64(X)))
+    L = B.lib()
+    assert L.tess_layernorm_row_sums(None, 4, 4, 4, B.BF16, None, 0, None) == 1
+    assert L.tess_layernorm_row_sums(sums.data_ptr(), 4, 8, 4, B.BF16, sums.data_ptr(), 0, None) == 3
+    assert L.tess_layernorm_normalize(sums.data_ptr(), 4, 8, 8, 7, sums.data_ptr(), 8, 1e-5,
+                                      sums.data_ptr(), 8, None) == 5
