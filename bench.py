@@ -31,6 +31,10 @@ def parse():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--all", action="store_true", help="also time every other bf16 workload")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --sweep: record one step (all calls of all layers) into a HIP graph "
+                         "after the warm-up and time replays of it, which removes the per-launch host "
+                         "cost that dominates the small strong-scaling shapes")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: one JSON line per grid of the paper's own "
                          "experiment tables (QKV, attention output and the two MLP layers at the "
@@ -115,7 +119,7 @@ class LayerState:
                                      workspace=self.ws)
 
 
-def time_workload(torch, tess, B, wl, w, steps, warmup, on_device=False):
+def time_workload(torch, tess, B, wl, w, steps, warmup, on_device=False, graph=False):
     layers = []
     for li, L in enumerate(w.layers):
         per_set = 2 * w.q * (L.m * L.kb + L.kb * L.n + L.m * L.n) + 2 * (L.m * L.n + L.m * L.kb) \
@@ -142,6 +146,29 @@ def time_workload(torch, tess, B, wl, w, steps, warmup, on_device=False):
     for s in range(warmup):
         step(s)
     torch.cuda.synchronize()
+    if graph:
+        # the library only enqueues kernels on the given stream (no allocation, no memset, no
+        # synchronisation), so a step can be recorded as it is; buffer set 0 is replayed
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step(0)
+        for _ in range(max(1, warmup)):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        flops_step = sum(3.0 * st.flops_call for st in layers)
+        ms_step = dt / steps * 1e3
+        return {"ms_per_step": ms_step, "tflops": flops_step / ms_step / 1e9, "calls": {},
+                "flops_step": flops_step, "layers": layers}
     # the timed region: K steps, with one HIP event on the launch stream at every call
     # boundary so that each call's average duration comes from these same launches
     marks = [[] for _ in range(steps)]
@@ -274,8 +301,9 @@ def main():
     if args.sweep:
         for ow in wl.PAPER_TABLE_WORKLOADS:
             torch.cuda.empty_cache()
-            r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, on_device=True)
-            print(json.dumps({"workload": ow.name, "grid": [ow.q, ow.q, ow.d],
+            r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, on_device=True,
+                              graph=args.graph)
+            print(json.dumps({"workload": ow.name, "grid": [ow.q, ow.q, ow.d], "graph_replay": args.graph,
                               "tflops": round(r["tflops"], 1), "ms_per_step": round(r["ms_per_step"], 4),
                               "calls": {k: {"MxNxK": v["MxNxK"], "tile": v["tile"], "k_splits": v["k_splits"],
                                             "ms": v["ms"], "tflops": v["tflops"]}

@@ -15,8 +15,6 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
     Plan p{};
     p.path = Path::Generic;
     p.bm = p.bn = 0;
-    p.bk = 64;
-    p.waves = 4;
     p.splits = 1;
     p.direct = 0;
     p.ws_bytes = 0;
@@ -54,14 +52,12 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
             if (cost < best) { best = cost; p.bm = p.bn = t; p.splits = sp; }
         }
     }
-    const int64_t tiles = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
     // tuning overrides, read at every call so that the workspace query and the launch agree
     if (const char* e = getenv("TESS_SPLITS")) { const int v = atoi(e); if (v >= 1 && kt_total / v >= 1) p.splits = v; }
     if (const char* e = getenv("TESS_TILE")) { const int v = atoi(e); if (v == 128 || (v == 256 && p.direct && M >= 256 && N >= 256)) p.bm = p.bn = v; }
-    const int64_t tiles2 = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
-    (void)tiles;
+    const int64_t tiles = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
     if (p.splits > 1)
-        p.ws_bytes = (size_t)p.splits * tiles2 * p.bm * p.bn * sizeof(float) +
+        p.ws_bytes = (size_t)p.splits * tiles * p.bm * p.bn * sizeof(float) +
                      (((size_t)p.splits * N * sizeof(float) + 255) & ~(size_t)255);   // + column sums
     return p;
 }

@@ -74,8 +74,6 @@ enum class Path : int32_t { Generic = 0, Mfma = 1 };
 struct Plan {
     Path path;
     int32_t bm, bn;     // macro tile of the MFMA path
-    int32_t bk;         // K extent of one LDS stage (64, or 32 with a deeper ring)
-    int32_t waves;      // wavefronts per workgroup of the 256 x 256 tile (8 or 4)
     int32_t splits;     // K splits (1 = none)
     int32_t direct;     // 1: global->LDS direct loads (needs Kp % 64 == 0)
     size_t ws_bytes;

@@ -185,3 +185,43 @@ def test_mfma_rate_probe_runs():
     torch.cuda.synchronize()
     assert flop == 8 * 4 * 10 * 8 * 32768.0
     assert torch.isfinite(sink).all()
+
+
+def test_calls_can_be_recorded_into_a_hip_graph():
+    """The library only enqueues kernels on the stream it is given (no allocation, no memset,
+    no synchronisation), so its calls can be recorded into a HIP graph.  Several replays, with
+    eager work and synchronisations in between, must reproduce the eager results bit for bit;
+    the shape makes the input-gradient call take the K-split path (workspace + reduction)."""
+    q, d, m, kb, n = 2, 2, 512, 256, 2048
+    inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=61, w_std=0.1)
+    desc = B.make_desc(q, d, 0, 0, 0, m * q * d, kb * q, n * q, B.BF16, B.BF16)
+    assert tess.plan(desc, B.OP_BWD_DX)[2] > 1
+    x, w, bias, dy = (dev(inp[k]) for k in ("x", "w", "bias", "dy"))
+    xl, wl_, dyl = list(x), list(w), list(dy)
+    nbytes = max(tess.workspace_bytes(desc, op) for op in (0, 1, 2))
+    ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device="cuda:0")
+    y = torch.empty((m, n), dtype=torch.bfloat16, device="cuda:0")
+    dx = torch.empty((m, kb), dtype=torch.bfloat16, device="cuda:0")
+    dw = torch.empty((kb, n), dtype=torch.bfloat16, device="cuda:0")
+
+    def calls():
+        tess.linear_fwd(desc, xl, wl_, bias, B.ACT_GELU_ERF, y, workspace=ws)
+        tess.linear_bwd_dx(desc, dyl, wl_, dx, workspace=ws)
+        tess.linear_bwd_dw(desc, xl, dyl, dw, workspace=ws)
+
+    calls()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (y, dx, dw)]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        calls()
+    for rep in range(3):
+        for t in (y, dx, dw):
+            t.fill_(float("nan"))                       # eager work between the replays
+        scratch = torch.randn(1 << 20, device="cuda:0").sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((y, dx, dw), want):
+            assert torch.equal(got, ref), rep
+        assert torch.isfinite(scratch)
