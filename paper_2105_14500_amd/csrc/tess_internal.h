@@ -50,8 +50,11 @@ struct GemmArgs {
 
 // Block -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each with its
 // own L2: the block ids that land on one XCD are relabelled to a contiguous run of tile
-// ids, and tile ids walk bands of 8 tile rows column by column, so that the 32 tiles an
-// XCD has in flight share 8 row panels and 4 column panels in its L2.  A bijection from
+// ids, and tile ids walk bands of GM tile rows column by column, so that the tiles an XCD
+// has in flight form a compact patch that shares row and column panels in its L2.  GM is
+// the band height (1..8) that needs the fewest panels, GM + c / GM for the c <= 32 tiles an
+// XCD runs at a time, preferring heights that divide the grid: 8 x 4 for 32 tiles (12
+// panels), 4 x 2 for 8 (6 panels where an 8 x 1 strip needs 9).  A bijection from
 // [0, tiles_m*tiles_n) onto the tile grid for every grid size.
 __host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
 {
@@ -59,7 +62,13 @@ __host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n,
     const int per = nb >> 3, rem = nb & 7;
     const int xcd = bid & 7, idx = bid >> 3;
     const int lid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
-    constexpr int GM = 8;
+    const int conc = per >= 32 ? 32 : (per >= 1 ? per : 1);   // tiles of one XCD in flight
+    int GM = 1, best = 1 << 30;
+    for (int gm = 1; gm <= 8 && gm <= tiles_m; ++gm) {
+        // panels x gm, so that the comparison stays in integers; ragged bands cost one more
+        const int cost = gm * gm + conc + (tiles_m % gm ? gm : 0);
+        if (cost * GM <= best * gm) { best = cost; GM = gm; }   // cost/gm <= best/GM, ties -> taller
+    }
     const int band = lid / (GM * tiles_n);
     const int first = band * GM;
     const int rows = tiles_m - first < GM ? tiles_m - first : GM;
