@@ -30,6 +30,9 @@ SHAPES = [
     (3, 1, 64, 64, 64, "f32"),
     (2, 2, 1024, 1024, 1024, "bf16"),  # 256x256 tiles
     (2, 1, 2048, 256, 2048, "bf16"),   # 256x256 tiles, many of them
+    (16, 1, 64, 64, 128, "bf16"),      # the largest grid dimension the ABI takes: 16 panels per operand
+    (8, 8, 128, 64, 256, "bf16"),      # d = q (the 3-D end of the family)
+    (16, 2, 24, 40, 56, "f32"),        # 16 panels through the fp32 kernel
 ]
 
 
