@@ -169,16 +169,21 @@ def time_workload(torch, tess, B, wl, w, steps, warmup, on_device=False, graph=F
         ms_step = dt / steps * 1e3
         return {"ms_per_step": ms_step, "tflops": flops_step / ms_step / 1e9, "calls": {},
                 "flops_step": flops_step, "layers": layers}
-    # the timed region: K steps, with one HIP event on the launch stream at every call
-    # boundary so that each call's average duration comes from these same launches
-    marks = [[] for _ in range(steps)]
+    # the timed region: exactly K steps between two synchronisations, nothing else enqueued
     t0 = time.perf_counter()
     for s in range(steps):
-        step(s, marks[s])
+        step(s)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     flops_step = sum(3.0 * st.flops_call for st in layers)
     ms_step = dt / steps * 1e3
+    # the same K steps once more with one HIP event on the launch stream at every call
+    # boundary: each call's average duration (an event between 20-microsecond kernels would
+    # distort the step time above, so the two passes are kept apart)
+    marks = [[] for _ in range(steps)]
+    for s in range(steps):
+        step(s, marks[s])
+    torch.cuda.synchronize()
 
     calls = {}
     ci = 0
