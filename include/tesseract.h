@@ -195,7 +195,9 @@ size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
  * 16-byte aligned: output macro tile and number of K splits (1 = the whole q-step
  * sum stays in one workgroup's registers; > 1 = partial sums go through the
  * workspace and a reduction kernel applies the epilogue).  tile 0 x 0 means the
- * plain fp32 kernel.  Pure host arithmetic. */
+ * plain fp32 kernel.  Pure host arithmetic.  For tuning sweeps the environment
+ * variables TESS_TILE (128 or 256) and TESS_SPLITS (>= 1) override the choice; they are
+ * read at every call, so this query, the workspace query and the launch agree. */
 tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int32_t* tile_n,
                              int32_t* k_splits);
 
