@@ -228,3 +228,29 @@ def test_calls_can_be_recorded_into_a_hip_graph():
         for got, ref in zip((y, dx, dw), want):
             assert torch.equal(got, ref), rep
         assert torch.isfinite(scratch)
+
+
+def _random_shapes(count, seed):
+    r = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(count):
+        q = int(r.integers(1, 6))
+        d = int(r.integers(1, q + 1))
+        # multiples of 8 (MFMA path, ragged tiles) with an occasional odd size (fp32-FMA path)
+        dims = [int(r.integers(1, 90)) * 8 for _ in range(3)]
+        if r.random() < 0.2:
+            dims[int(r.integers(0, 3))] += int(r.integers(1, 8))
+        shapes.append((q, d, *dims))
+    return shapes
+
+
+@pytest.mark.parametrize("q,d,m,kb,n", _random_shapes(24, 2024))
+def test_random_block_shapes(q, d, m, kb, n):
+    """Seeded random block shapes: ragged tile edges in every direction, contraction lengths
+    that are and are not multiples of the 64-deep stage, K-split and single-launch plans."""
+    inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=m * 7 + kb * 3 + n, w_std=0.05)
+    got = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "f32", act="gelu_erf")
+    want = oracle_share(inp["x"], inp["w"], inp["bias"], inp["dy"], act="gelu_erf")
+    for key in ("y", "dx", "dw"):
+        e = rel_err(got[key], want[key])
+        assert e <= 1e-5, (key, e)
