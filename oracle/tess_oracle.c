@@ -354,6 +354,41 @@ void orc_layernorm_from_sums(const double* x, int64_t m, int64_t w, int64_t ldx,
     }
 }
 
+/* Backward of the normalisation (the X' equation of the same passage): with
+ * g = dJ/dxhat and n the full hidden size,
+ *   X' = ( g - ( xhat * sum_j(xhat_j g_j) + sum_j g_j ) / n ) / sqrt(Var[X] + eps).
+ * The two row sums are again local partial sums that are reduced along the grid
+ * row; Var comes from the forward sums S1, S2.                                */
+void orc_row_sums_bwd(const double* xhat, const double* g, int64_t m, int64_t w, int64_t ldx,
+                      int64_t ldg, int accumulate, double* sums_out /* [m, 2] */)
+{
+    for (int64_t r = 0; r < m; ++r) {
+        double a = 0.0, b = 0.0;
+        for (int64_t u = 0; u < w; ++u) {
+            a += xhat[r * ldx + u] * g[r * ldg + u];
+            b += g[r * ldg + u];
+        }
+        sums_out[2 * r] = accumulate ? sums_out[2 * r] + a : a;
+        sums_out[2 * r + 1] = accumulate ? sums_out[2 * r + 1] + b : b;
+    }
+}
+
+void orc_layernorm_bwd_from_sums(const double* xhat, const double* g, int64_t m, int64_t w,
+                                 int64_t ldx, int64_t ldg, const double* sums_bwd,
+                                 const double* sums_fwd, int64_t n_total, double eps,
+                                 double* dx_out /* [m, w] packed */)
+{
+    for (int64_t r = 0; r < m; ++r) {
+        const double mean = sums_fwd[2 * r] / (double)n_total;
+        const double var = sums_fwd[2 * r + 1] / (double)n_total - mean * mean;
+        const double rstd = 1.0 / sqrt(var + eps);
+        for (int64_t u = 0; u < w; ++u) {
+            const double xh = xhat[r * ldx + u];
+            dx_out[r * w + u] = (g[r * ldg + u] - (xh * sums_bwd[2 * r] + sums_bwd[2 * r + 1]) / (double)n_total) * rstd;
+        }
+    }
+}
+
 /* ---- per-processor formulas on the unpartitioned matrices ----------------
  * These cut the blocks out of the global matrices exactly as Alg. 3 lays
  * them out and hand them to the panel formulas above.                       */

@@ -61,6 +61,11 @@ def lib():
         L.orc_row_sums.restype = None
         L.orc_layernorm_from_sums.argtypes = [dp, i64, i64, i64, dp, i64, ctypes.c_double, dp]
         L.orc_layernorm_from_sums.restype = None
+        L.orc_row_sums_bwd.argtypes = [dp, dp, i64, i64, i64, i64, ctypes.c_int, dp]
+        L.orc_row_sums_bwd.restype = None
+        L.orc_layernorm_bwd_from_sums.argtypes = [dp, dp, i64, i64, i64, i64, dp, dp, i64,
+                                                  ctypes.c_double, dp]
+        L.orc_layernorm_bwd_from_sums.restype = None
         L.orc_tess_fwd.argtypes = [ctypes.c_int] * 5 + [i64] * 3 + [dp, dp, dp, ctypes.c_int,
                                                                    dp, dp]
         L.orc_tess_fwd.restype = ctypes.c_int
@@ -266,6 +271,31 @@ def layernorm_from_sums(x, sums, n_total, eps):
     assert sums.shape == (m, 2)
     out = np.empty((m, w))
     lib().orc_layernorm_from_sums(_p(x), m, w, w, _p(sums), n_total, float(eps), _p(out))
+    return out
+
+
+def row_sums_bwd(xhat, g, accumulate_into=None):
+    """[m, 2]: per row sum(xhat * g) and sum(g) of one block."""
+    xhat, g = _f64(xhat), _f64(g)
+    m, w = xhat.shape
+    assert g.shape == (m, w)
+    if accumulate_into is not None:
+        out = accumulate_into
+        assert out.dtype == np.float64 and out.shape == (m, 2) and out.flags.c_contiguous
+        acc = 1
+    else:
+        out = np.empty((m, 2))
+        acc = 0
+    lib().orc_row_sums_bwd(_p(xhat), _p(g), m, w, w, w, acc, _p(out))
+    return out
+
+
+def layernorm_bwd_from_sums(xhat, g, sums_bwd, sums_fwd, n_total, eps):
+    xhat, g, sums_bwd, sums_fwd = _f64(xhat), _f64(g), _f64(sums_bwd), _f64(sums_fwd)
+    m, w = xhat.shape
+    out = np.empty((m, w))
+    lib().orc_layernorm_bwd_from_sums(_p(xhat), _p(g), m, w, w, w, _p(sums_bwd), _p(sums_fwd), n_total,
+                                      float(eps), _p(out))
     return out
 
 

@@ -535,3 +535,43 @@ def test_row_sums_and_layernorm_against_numpy():
     assert s.tolist() == [[12.0, 50.0]]
     got = orc.layernorm_from_sums(np.array([[1.0, 2.0, 3.0, 6.0]]), s, 4, 0.0)
     assert np.allclose(got, np.array([[-2.0, -1.0, 0.0, 3.0]]) / np.sqrt(3.5), atol=1e-15)
+
+
+def test_layernorm_backward_against_central_differences():
+    """X' of the paper's formula is the gradient of J = sum(c * xhat(X)) for fixed weights c
+    (so dJ/dxhat = c): central differences of the oracle's own forward, element by element,
+    with the hidden dimension spread over q blocks."""
+    q, m, w = 2, 3, 4
+    n, eps = q * w, 1e-3
+    r = _rng(71)
+    X = r.standard_normal((m, n)) * 2 + 0.5
+    C = r.standard_normal((m, n))
+
+    def forward(Xm):
+        s = np.zeros((m, 2))
+        for j in range(q):
+            orc.row_sums(np.ascontiguousarray(Xm[:, j * w:(j + 1) * w]), accumulate_into=s)
+        xh = np.concatenate([orc.layernorm_from_sums(np.ascontiguousarray(Xm[:, j * w:(j + 1) * w]), s, n, eps)
+                             for j in range(q)], axis=1)
+        return xh, s
+
+    xhat, s_fwd = forward(X)
+    s_bwd = np.zeros((m, 2))
+    for j in range(q):
+        orc.row_sums_bwd(np.ascontiguousarray(xhat[:, j * w:(j + 1) * w]),
+                         np.ascontiguousarray(C[:, j * w:(j + 1) * w]), accumulate_into=s_bwd)
+    assert np.allclose(s_bwd[:, 0], (xhat * C).sum(axis=1), atol=1e-13)
+    assert np.allclose(s_bwd[:, 1], C.sum(axis=1), atol=1e-13)
+    got = np.concatenate([orc.layernorm_bwd_from_sums(np.ascontiguousarray(xhat[:, j * w:(j + 1) * w]),
+                                                      np.ascontiguousarray(C[:, j * w:(j + 1) * w]),
+                                                      s_bwd, s_fwd, n, eps) for j in range(q)], axis=1)
+    h = 1e-6
+    for rr in range(m):
+        for u in range(n):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[rr, u] += h
+            Xm[rr, u] -= h
+            fd = (np.sum(C * forward(Xp)[0]) - np.sum(C * forward(Xm)[0])) / (2 * h)
+            assert abs(fd - got[rr, u]) < 1e-7, (rr, u)
+    # the gradient is orthogonal to the all-ones direction (shifting a row changes nothing)
+    assert np.allclose(got.sum(axis=1), 0.0, atol=1e-12)
