@@ -185,6 +185,22 @@ tess_status tess_layernorm_normalize(const void* x, int64_t m, int64_t w, int64_
                                      const void* sums, int64_t n_total, float eps,
                                      void* xhat_out, int64_t ldo, void* hip_stream);
 
+/* Backward of the same normalisation (the X' equation of Section 3.2, "Other procedure"):
+ * with g = dJ/dxhat,  X' = (g - (xhat * sum(xhat g) + sum(g)) / n) / sqrt(Var[X] + eps).
+ * The two row sums are local partial sums that the caller reduces along the grid row
+ * (`accumulate` adds a further block's sums).
+ *   xhat, g  : device, [m, w] in `dtype`, ldx / ldg
+ *   sums_out : device, [m, 2] fp32: sum(xhat * g), sum(g)                              */
+tess_status tess_layernorm_bwd_row_sums(const void* xhat, int64_t ldx, const void* g, int64_t ldg,
+                                        int64_t m, int64_t w, int dtype, void* sums_out,
+                                        int accumulate, void* hip_stream);
+/* X' of one block from the REDUCED backward sums and the REDUCED forward sums (which give
+ * Var[X]); dx_out: device, [m, w] in `dtype`, ldo; may equal g.                         */
+tess_status tess_layernorm_bwd_apply(const void* xhat, int64_t ldx, const void* g, int64_t ldg,
+                                     int64_t m, int64_t w, int dtype, const void* sums_bwd,
+                                     const void* sums_fwd, int64_t n_total, float eps,
+                                     void* dx_out, int64_t ldo, void* hip_stream);
+
 /* Bytes of device scratch that the call `op` (a tess_op) needs for this
  * descriptor on the current device (0 when none).  TESS_OP_BWD_DX also covers
  * tess_linear_bwd_dx_act and TESS_OP_BWD_DW covers tess_linear_bwd_dw_bias; the *_STEP

@@ -22,6 +22,7 @@ EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
            "tess_linear_bwd_dx_act", "tess_linear_bwd_dw_bias",
            "tess_linear_bwd_dx_step", "tess_linear_bwd_dw_step",
            "tess_layernorm_row_sums", "tess_layernorm_normalize",
+           "tess_layernorm_bwd_row_sums", "tess_layernorm_bwd_apply",
            "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate",
            "tess_tile_of_block", "tess_desc_check", "tess_block_shape",
            "tess_status_string", "tess_version"]
@@ -72,6 +73,11 @@ def lib():
         L.tess_layernorm_row_sums.argtypes = [vp, i64, i64, i64, cint, vp, cint, vp]
         L.tess_layernorm_normalize.restype = cint
         L.tess_layernorm_normalize.argtypes = [vp, i64, i64, i64, cint, vp, i64, ctypes.c_float, vp, i64, vp]
+        L.tess_layernorm_bwd_row_sums.restype = cint
+        L.tess_layernorm_bwd_row_sums.argtypes = [vp, i64, vp, i64, i64, i64, cint, vp, cint, vp]
+        L.tess_layernorm_bwd_apply.restype = cint
+        L.tess_layernorm_bwd_apply.argtypes = [vp, i64, vp, i64, i64, i64, cint, vp, vp, i64,
+                                               ctypes.c_float, vp, i64, vp]
         L.tess_linear_workspace_bytes.restype = sz
         L.tess_linear_workspace_bytes.argtypes = [dp, cint]
         i32p = ctypes.POINTER(ctypes.c_int32)
@@ -188,6 +194,37 @@ def layernorm_normalize(x, sums, n_total, eps, xhat_out, stream=None):
                                         _stream(stream))
     if st:
         raise TessError(st, "tess_layernorm_normalize")
+
+
+def _sums(t, m, what):
+    if t.dtype != torch.float32 or tuple(t.shape) != (m, 2) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{what}: need a contiguous device float32 tensor of shape (m, 2)")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def layernorm_bwd_row_sums(xhat, g, sums_out, accumulate=False, stream=None):
+    """tess_layernorm_bwd_row_sums: sums_out[m, 2] (+)= per-row sum(xhat * g), sum(g)."""
+    m, w = xhat.shape
+    xp, ldx = _out(xhat, m, w, "xhat")
+    gp, ldg = _out(g, m, w, "g")
+    st = lib().tess_layernorm_bwd_row_sums(xp, ldx, gp, ldg, m, w, dtype_code(xhat.dtype),
+                                           _sums(sums_out, m, "sums_out"), 1 if accumulate else 0,
+                                           _stream(stream))
+    if st:
+        raise TessError(st, "tess_layernorm_bwd_row_sums")
+
+
+def layernorm_bwd_apply(xhat, g, sums_bwd, sums_fwd, n_total, eps, dx_out, stream=None):
+    """tess_layernorm_bwd_apply: dx_out = (g - (xhat * A + B) / n) / sqrt(var + eps)."""
+    m, w = xhat.shape
+    xp, ldx = _out(xhat, m, w, "xhat")
+    gp, ldg = _out(g, m, w, "g")
+    op, ldo = _out(dx_out, m, w, "dx_out")
+    st = lib().tess_layernorm_bwd_apply(xp, ldx, gp, ldg, m, w, dtype_code(xhat.dtype),
+                                        _sums(sums_bwd, m, "sums_bwd"), _sums(sums_fwd, m, "sums_fwd"),
+                                        n_total, float(eps), op, ldo, _stream(stream))
+    if st:
+        raise TessError(st, "tess_layernorm_bwd_apply")
 
 
 def _panel_array(panels, rows, cols, what):

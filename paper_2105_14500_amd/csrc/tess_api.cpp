@@ -363,6 +363,35 @@ tess_status tess_layernorm_normalize(const void* x, int64_t m, int64_t w, int64_
     return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
 }
 
+tess_status tess_layernorm_bwd_row_sums(const void* xhat, int64_t ldx, const void* g, int64_t ldg,
+                                        int64_t m, int64_t w, int dtype, void* sums_out,
+                                        int accumulate, void* hip_stream)
+{
+    if (!xhat || !g || !sums_out) return TESS_ERR_NULL;
+    if (m < 1 || w < 1 || ldx < w || ldg < w || m > ((int64_t)1 << 32)) return TESS_ERR_SHAPE;
+    if ((dtype != TESS_F32 && dtype != TESS_BF16) || (accumulate != 0 && accumulate != 1))
+        return TESS_ERR_UNSUPPORTED;
+    hipError_t e = launch_row_sums_bwd(xhat, g, m, w, ldx, ldg, dtype == TESS_F32, accumulate,
+                                       static_cast<float*>(sums_out), static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
+}
+
+tess_status tess_layernorm_bwd_apply(const void* xhat, int64_t ldx, const void* g, int64_t ldg,
+                                     int64_t m, int64_t w, int dtype, const void* sums_bwd,
+                                     const void* sums_fwd, int64_t n_total, float eps,
+                                     void* dx_out, int64_t ldo, void* hip_stream)
+{
+    if (!xhat || !g || !sums_bwd || !sums_fwd || !dx_out) return TESS_ERR_NULL;
+    if (m < 1 || w < 1 || ldx < w || ldg < w || ldo < w || n_total < w || m > ((int64_t)1 << 32))
+        return TESS_ERR_SHAPE;
+    if ((dtype != TESS_F32 && dtype != TESS_BF16) || !(eps >= 0.0f)) return TESS_ERR_UNSUPPORTED;
+    hipError_t e = launch_layernorm_bwd(xhat, g, m, w, ldx, ldg, dtype == TESS_F32,
+                                        static_cast<const float*>(sums_bwd),
+                                        static_cast<const float*>(sums_fwd), 1.0f / (float)n_total, eps,
+                                        dx_out, ldo, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
+}
+
 tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream)
 {
     if (!sink) return TESS_ERR_NULL;

@@ -97,6 +97,11 @@ hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s);
 hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, hipStream_t s);
 hipError_t launch_row_sums(const void* x, int64_t m, int64_t w, int64_t ldx, int in_f32,
                            int accumulate, float* out, hipStream_t s);
+hipError_t launch_row_sums_bwd(const void* xhat, const void* g, int64_t m, int64_t w, int64_t ldx,
+                               int64_t ldg, int in_f32, int accumulate, float* out, hipStream_t s);
+hipError_t launch_layernorm_bwd(const void* xhat, const void* g, int64_t m, int64_t w, int64_t ldx,
+                                int64_t ldg, int in_f32, const float* sums_bwd, const float* sums_fwd,
+                                float inv_n, float eps, void* out, int64_t ldo, hipStream_t s);
 hipError_t launch_normalize(const void* x, int64_t m, int64_t w, int64_t ldx, int in_f32,
                             const float* sums, float inv_n, float eps, void* out, int64_t ldo,
                             hipStream_t s);

@@ -50,3 +50,46 @@ def test_row_sums_of_integers_are_exact_and_errors_are_reported():
     assert L.tess_layernorm_row_sums(sums.data_ptr(), 4, 8, 4, B.BF16, sums.data_ptr(), 0, None) == 3
     assert L.tess_layernorm_normalize(sums.data_ptr(), 4, 8, 8, 7, sums.data_ptr(), 8, 1e-5,
                                       sums.data_ptr(), 8, None) == 5
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("q,m,w", [(1, 7, 33), (2, 5, 8), (4, 256, 1024), (3, 130, 72)])
+def test_backward_row_sums_and_apply(dtype, q, m, w):
+    """The backward of the normalisation on the q column blocks of whole rows: partial sums
+    accumulated over the blocks, then X' per block, against the fp64 oracle."""
+    g_ = torch.Generator().manual_seed(15 + q + m)
+    X = (torch.randn((m, q * w), generator=g_) * 2 + 0.5).to(tdtype(dtype))
+    G = torch.randn((m, q * w), generator=g_).to(tdtype(dtype))
+    n, eps = q * w, 1e-5
+    Xd, Gd = dev(X), dev(G)
+    s_fwd = torch.empty((m, 2), device="cuda:0")
+    for j in range(q):
+        B.layernorm_row_sums(Xd[:, j * w:(j + 1) * w], s_fwd, accumulate=(j > 0))
+    xhat = torch.empty_like(Xd)
+    for j in range(q):
+        B.layernorm_normalize(Xd[:, j * w:(j + 1) * w], s_fwd, n, eps, xhat[:, j * w:(j + 1) * w])
+    s_bwd = torch.full((m, 2), float("nan"), device="cuda:0")
+    for j in range(q):
+        B.layernorm_bwd_row_sums(xhat[:, j * w:(j + 1) * w], Gd[:, j * w:(j + 1) * w], s_bwd,
+                                 accumulate=(j > 0))
+    dx = torch.full((m, n), float("nan"), dtype=tdtype(dtype), device="cuda:0")
+    for j in range(q):
+        B.layernorm_bwd_apply(xhat[:, j * w:(j + 1) * w], Gd[:, j * w:(j + 1) * w], s_bwd, s_fwd, n, eps,
+                              dx[:, j * w:(j + 1) * w])
+    torch.cuda.synchronize()
+    # the oracle takes the GPU-independent inputs: X, G, and ITS OWN forward
+    X64, G64 = f64(X), f64(G)
+    blk = lambda M_, j: np.ascontiguousarray(M_[:, j * w:(j + 1) * w])
+    sf = np.zeros((m, 2))
+    for j in range(q):
+        orc.row_sums(blk(X64, j), accumulate_into=sf)
+    xh = np.concatenate([orc.layernorm_from_sums(blk(X64, j), sf, n, eps) for j in range(q)], axis=1)
+    sb = np.zeros((m, 2))
+    for j in range(q):
+        orc.row_sums_bwd(blk(xh, j), blk(G64, j), accumulate_into=sb)
+    want = np.concatenate([orc.layernorm_bwd_from_sums(blk(xh, j), blk(G64, j), sb, sf, n, eps)
+                           for j in range(q)], axis=1)
+    tol = TOL["bf16"] if dtype == "bf16" else 1e-4
+    assert rel_err(s_bwd, sb) <= tol          # xhat is rounded to the storage dtype on the GPU
+    assert rel_err(dx, want) <= tol
+    assert not torch.isnan(dx).any()
