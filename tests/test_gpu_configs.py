@@ -65,7 +65,8 @@ def test_one_share_full_size(wname, lname):
     xs = [f64(inp["x"][t][rows]) for t in range(q)]
     wcols = [f64(inp["w"][t][:, c0:c0 + cw]) for t in range(q)]
     want = orc.fwd_panels(xs, wcols, bias=f64(inp["bias"][c0:c0 + cw]), act=oact)
-    e = rel_err(y[rows][:, c0:c0 + cw], want)
+    errs = {}
+    e = errs["y"] = rel_err(y[rows][:, c0:c0 + cw], want)
     assert e <= TOL["bf16"], ("y", e)
     # dX[rows, u0:u0+uw]
     u0 = (kb // 2 // 8) * 8 - 64 if kb >= 512 else 0
@@ -73,7 +74,7 @@ def test_one_share_full_size(wname, lname):
     dys = [f64(inp["dy"][t][rows]) for t in range(q)]
     wrows = [f64(inp["w"][t][u0:u0 + uw]) for t in range(q)]
     want = orc.bwd_dx_panels(dys, wrows)
-    e = rel_err(dx[rows][:, u0:u0 + uw], want)
+    e = errs["dx"] = rel_err(dx[rows][:, u0:u0 + uw], want)
     assert e <= TOL["bf16"], ("dx", e)
     # dW[urows, c0:c0+cw2]
     urows = _sample(kb, 12, 2)
@@ -81,7 +82,7 @@ def test_one_share_full_size(wname, lname):
     xcols = [np.ascontiguousarray(f64(inp["x"][t][:, urows])) for t in range(q)]
     dyw = [f64(inp["dy"][t][:, c0:c0 + cw2]) for t in range(q)]
     want = orc.bwd_dw_panels(xcols, dyw)
-    e = rel_err(dw[urows][:, c0:c0 + cw2], want)
+    e = errs["dw"] = rel_err(dw[urows][:, c0:c0 + cw2], want)
     assert e <= 1e-3, ("dw", e)            # fp32 output: accumulation order only
 
     # the backward epilogues next to the path, same buffers and workspace:
@@ -97,12 +98,14 @@ def test_one_share_full_size(wname, lname):
     torch.cuda.synchronize()
     assert torch.equal(dw2, dw)
     want = orc.bias_grad_panels([np.ascontiguousarray(p) for p in dyw])
-    e = rel_err(db[c0:c0 + cw2], want)
+    e = errs["db"] = rel_err(db[c0:c0 + cw2], want)
     assert e <= 1e-4, ("db", e)
     assert not torch.isnan(dz).any()
     want = orc.bwd_dx_act_panels(dys, wrows, f64(z[rows][:, u0:u0 + uw]), orc.ACT_GELU_ERF)
     e = rel_err(dz[rows][:, u0:u0 + uw], want)
     assert e <= TOL["bf16"], ("dz", e)
+    # one line per case for the results table (shown with pytest -s)
+    print(f"\nPARITY {wname} {lname} " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()) + f" dz={e:.2e}")
 
 
 def test_config1_full_grid_fp32():
