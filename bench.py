@@ -424,6 +424,15 @@ def main():
                                "ms_per_step": round(r["ms_per_step"], 4), "calls": r["calls"]}
             del r
         out["other_workloads"] = others
+    elif w.name == DEFAULT_WORKLOAD:
+        # the small MLP up-projection configuration (launch-bound: 8.6 GFLOP per call) is cheap
+        # enough to ride along with every default run
+        ow = wl.workload_by_name("cfg2_q2d2_bf16_mlp_up_h1024")
+        r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup)
+        out["other_workloads"] = {ow.name: {"tflops": round(r["tflops"], 2),
+                                            "pct_peak": round(100.0 * r["tflops"] / PEAK_BF16_TFLOPS, 2),
+                                            "ms_per_step": round(r["ms_per_step"], 4), "calls": r["calls"]}}
+        del r
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(torch, w, layers0[0])
     print(json.dumps(out))
