@@ -902,13 +902,21 @@ __global__ __launch_bounds__(256) void tess_splitk_reduce_kernel(GemmArgs g)
         sum += v0; sum += v1; sum += v2; sum += v3;
     }
     for (; z < g.splits; ++z) sum += w[(size_t)z * zstride];
+    // the same epilogue as the single-launch path: four adjacent columns per thread, vector
+    // loads and stores when the output rows allow it
+    floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
+    if (g.bias) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        if (col + e < g.N) {
-            const float bv = g.bias ? bf16_bits_to_f32(((const uint16_t*)g.bias)[col + e]) : 0.0f;
-            store_out(g, row, col + e, sum[e], bv);
-        }
+        for (int e = 0; e < 4; ++e)
+            if (col + e < g.N) bias4[e] = bf16_bits_to_f32(((const uint16_t*)g.bias)[col + e]);
     }
+    const int esize = g.out_f32 ? 4 : 2;
+    const bool vec = ((g.ldo * esize) % 16 == 0) && ((reinterpret_cast<uintptr_t>(g.out) & 15u) == 0) &&
+                     (!g.preact || (reinterpret_cast<uintptr_t>(g.preact) & 15u) == 0);
+    if (g.out_f32 && g.accumulate && !g.zin && !g.preact && g.act == TESS_ACT_NONE)
+        emit4<MODE_F32_ACC>(g, row, col, sum, bias4, vec);
+    else
+        emit4<MODE_GENERIC>(g, row, col, sum, bias4, vec);
 }
 
 template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT,
