@@ -433,6 +433,11 @@ def main():
                                             "pct_peak": round(100.0 * r["tflops"] / PEAK_BF16_TFLOPS, 2),
                                             "ms_per_step": round(r["ms_per_step"], 4), "calls": r["calls"]}}
         del r
+        # the same step replayed from a HIP graph: what is left once the per-launch host cost is gone
+        rg = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, graph=True)
+        out["other_workloads"][ow.name]["graph_replay"] = {"tflops": round(rg["tflops"], 2),
+                                                           "ms_per_step": round(rg["ms_per_step"], 4)}
+        del rg
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(torch, w, layers0[0])
     print(json.dumps(out))
