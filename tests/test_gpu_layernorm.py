@@ -93,3 +93,27 @@ def test_backward_row_sums_and_apply(dtype, q, m, w):
     assert rel_err(s_bwd, sb) <= tol          # xhat is rounded to the storage dtype on the GPU
     assert rel_err(dx, want) <= tol
     assert not torch.isnan(dx).any()
+
+
+def test_in_place_variants():
+    """xhat_out may be x itself and dx_out may be g itself (each element is read once, by the lane
+    that overwrites it)."""
+    m, w, eps = 96, 520, 1e-5
+    g_ = torch.Generator().manual_seed(9)
+    X = (torch.randn((m, w), generator=g_) * 2 + 1).to(torch.bfloat16)
+    G = torch.randn((m, w), generator=g_).to(torch.bfloat16)
+    Xd, Gd = dev(X), dev(G)
+    s_fwd = torch.empty((m, 2), device="cuda:0")
+    B.layernorm_row_sums(Xd, s_fwd)
+    out = torch.empty_like(Xd)
+    B.layernorm_normalize(Xd, s_fwd, w, eps, out)
+    inplace = Xd.clone()
+    B.layernorm_normalize(inplace, s_fwd, w, eps, inplace)
+    s_bwd = torch.empty((m, 2), device="cuda:0")
+    B.layernorm_bwd_row_sums(out, Gd, s_bwd)
+    dx = torch.empty_like(Gd)
+    B.layernorm_bwd_apply(out, Gd, s_bwd, s_fwd, w, eps, dx)
+    g_inplace = Gd.clone()
+    B.layernorm_bwd_apply(out, g_inplace, s_bwd, s_fwd, w, eps, g_inplace)
+    torch.cuda.synchronize()
+    assert torch.equal(inplace, out) and torch.equal(g_inplace, dx)
