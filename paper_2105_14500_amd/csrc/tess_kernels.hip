@@ -8,6 +8,7 @@
 //   * tess_generic_kernel  any shape / alignment / fp32 inputs, fp32 FMA.
 #include "tess_internal.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace tess {
@@ -926,12 +927,17 @@ static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
     constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
     constexpr int NT = 64 * WGM * WGN;
     auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT, COLSUM>;
-    static bool attr_set = false;   // per instantiation; the attribute is idempotent
-    if (!attr_set) {
+    // the dynamic LDS limit is a per-device attribute of the kernel: set it once per device
+    // (a bit per device id; setting it twice from two threads is harmless)
+    static std::atomic<uint64_t> attr_done{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (dev > 63 || !(attr_done.load(std::memory_order_acquire) & bit)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            lds_bytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_done.fetch_or(bit, std::memory_order_release);
     }
     const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     GemmArgs a = g;
