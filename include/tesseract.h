@@ -20,7 +20,8 @@
  *    are shared by the q panels of one operand, so a panel may be a packed
  *    receive buffer (ld = row length) or a view into a larger matrix.
  *  - Ownership: the caller owns every buffer, including the workspace.  The
- *    library allocates nothing, keeps no state between calls and never
+ *    library allocates nothing, keeps no state between calls (apart from having
+ *    set a launch attribute of its kernels once per device) and never
  *    synchronises; kernels are enqueued on `hip_stream` (a hipStream_t cast to
  *    void*, NULL = the default stream) of the current device.
  *  - Errors: a status code is returned, nothing is thrown or aborted.  All
