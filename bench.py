@@ -363,7 +363,10 @@ def main():
                      "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4),
                      "flop_per_launch": dom_layer.flops_call, "avg_ms": dom["ms"],
-                     "traffic": traffic},
+                     "traffic": traffic,
+                     # context: the rate a register-resident MFMA-only loop reached in this run
+                     "mfma_only_loop": round(mfma_only, 1),
+                     "frac_of_mfma_only_loop": round(dom["tflops"] / mfma_only, 4)},
     }
     if args.mlp_chain:
         by_name = {L.name: L for L in w.layers}
