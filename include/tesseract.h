@@ -50,7 +50,8 @@ typedef enum {
     TESS_ERR_NULL = 1,        /* a required pointer (descriptor, panel, output) is NULL      */
     TESS_ERR_GRID = 2,        /* q<1, d<1, d>q, q>TESS_MAX_Q or a coordinate outside the grid */
     TESS_ERR_SHAPE = 3,       /* a%(q*d), b%q or c%q non-zero, a size < 1, or ld < row length */
-    TESS_ERR_ALIGN = 4,       /* reserved: alignment the selected kernel cannot serve         */
+    TESS_ERR_ALIGN = 4,       /* bf16 matrix-core plan, but a panel pointer is not 16-byte
+                                 aligned or a leading dimension is no multiple of 8          */
     TESS_ERR_UNSUPPORTED = 5, /* dtype / activation / flag combination not implemented        */
     TESS_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than tess_linear_workspace_bytes   */
     TESS_ERR_HIP = 7          /* a HIP runtime call (kernel launch) failed                    */
@@ -208,28 +209,16 @@ tess_status tess_layernorm_bwd_apply(const void* xhat, int64_t ldx, const void* 
  * codes are the single-step partial products.  Pure host arithmetic. */
 size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
 
-/* Launch shape that the call `op` would use for this descriptor when operands are
- * 16-byte aligned: output macro tile and number of K splits (1 = the whole q-step
- * sum stays in one workgroup's registers; > 1 = partial sums go through the
- * workspace and a reduction kernel applies the epilogue).  tile 0 x 0 means the
- * plain fp32 kernel.  Pure host arithmetic.  For tuning sweeps the environment
- * variables TESS_TILE (128 or 256) and TESS_SPLITS (>= 1) override the choice; they are
- * read at every call, so this query, the workspace query and the launch agree. */
+/* Launch shape that the call `op` would use for this descriptor: output macro tile and
+ * number of K splits (1 = the whole q-step sum stays in one workgroup's registers; > 1 =
+ * partial sums go through the workspace and are summed in ascending split order before
+ * the epilogue).  tile 0 x 0 means the plain fp32 kernel: fp32 inputs, or a bf16 block
+ * whose contiguous extents are no multiple of 8.  Pure host arithmetic.  A call whose
+ * plan uses the matrix cores needs 16-byte aligned panel pointers and leading dimensions
+ * that are multiples of 8 elements, and returns TESS_ERR_ALIGN otherwise (it never drops
+ * to the plain kernel silently); a panel of 4 GiB or more returns TESS_ERR_UNSUPPORTED. */
 tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int32_t* tile_n,
                              int32_t* k_splits);
-
-/* Measurement aid: enqueues a register-resident loop of bf16 32x32x16 MFMAs (no
- * memory traffic) on `workgroups` workgroups of 256 threads, `iters` x 8 MFMAs per
- * wavefront, and writes one float per thread to `sink` (device, workgroups*256 floats)
- * so that the loop is not optimised away.  Timing it gives the matrix-core rate this
- * device sustains at its actual clock: workgroups * 4 * iters * 8 * 32768 flop.   */
-tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream);
-
-/* Diagnostic: the output tile (tile row *tm, tile column *tn) that workgroup `block` of
- * a launch over a tiles_m x tiles_n tile grid computes.  The same function the kernels
- * use; a bijection from [0, tiles_m*tiles_n) onto the grid.  Pure host arithmetic. */
-tess_status tess_tile_of_block(int32_t block, int32_t tiles_m, int32_t tiles_n, int32_t* tm,
-                               int32_t* tn);
 
 /* Validates a descriptor alone (grid rules and divisibility). */
 tess_status tess_desc_check(const tess_desc* desc);

@@ -24,7 +24,7 @@ EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
            "tess_layernorm_row_sums", "tess_layernorm_normalize",
            "tess_layernorm_bwd_row_sums", "tess_layernorm_bwd_apply",
            "tess_linear_workspace_bytes", "tess_linear_plan", "tess_probe_mfma_rate",
-           "tess_tile_of_block", "tess_desc_check", "tess_block_shape",
+           "tess_tile_of_block", "tess_diag_set_plan_override", "tess_desc_check", "tess_block_shape",
            "tess_status_string", "tess_version"]
 
 
@@ -84,7 +84,9 @@ def lib():
         L.tess_linear_plan.restype = cint
         L.tess_linear_plan.argtypes = [dp, cint, i32p, i32p, i32p]
         L.tess_probe_mfma_rate.restype = cint
-        L.tess_probe_mfma_rate.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
+        L.tess_probe_mfma_rate.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]
+        L.tess_diag_set_plan_override.restype = cint
+        L.tess_diag_set_plan_override.argtypes = [ctypes.c_int32, ctypes.c_int32]
         L.tess_tile_of_block.restype = cint
         L.tess_tile_of_block.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_int32)] * 2
         L.tess_desc_check.restype = cint
@@ -156,15 +158,23 @@ def tile_of_block(block, tiles_m, tiles_n):
     return tm.value, tn.value
 
 
-def probe_mfma_rate(sink, workgroups, iters, stream=None):
-    """tess_probe_mfma_rate: enqueue the register-resident MFMA loop; returns its flop count."""
+def probe_mfma_rate(sink, workgroups, iters, real_data=False, stream=None):
+    """tess_probe_mfma_rate: enqueue the register-resident MFMA loop; returns its flop count.
+    real_data: operands distributed like the workloads' instead of small integers."""
     if sink.numel() < workgroups * 256 or sink.dtype != torch.float32 or not sink.is_cuda:
         raise ValueError("sink: need a device float32 tensor of workgroups*256 elements")
     st = lib().tess_probe_mfma_rate(ctypes.c_void_p(sink.data_ptr()), workgroups, iters,
-                                    _stream(stream))
+                                    1 if real_data else 0, _stream(stream))
     if st:
         raise TessError(st, "tess_probe_mfma_rate")
-    return workgroups * 4 * iters * 8 * 32768.0
+    return workgroups * 4 * iters * 16 * 32768.0
+
+
+def set_plan_override(tile=0, k_splits=0):
+    """tess_diag_set_plan_override: force tile (128/256) and K splits of later calls; 0 = cost model."""
+    st = lib().tess_diag_set_plan_override(tile, k_splits)
+    if st:
+        raise TessError(st, "tess_diag_set_plan_override")
 
 
 def layernorm_row_sums(x, sums_out, accumulate=False, stream=None):
@@ -227,12 +237,33 @@ def layernorm_bwd_apply(xhat, g, sums_bwd, sums_fwd, n_total, eps, dx_out, strea
         raise TessError(st, "tess_layernorm_bwd_apply")
 
 
-def _panel_array(panels, rows, cols, what):
+_TORCH_DTYPE = {F32: torch.float32, BF16: torch.bfloat16}
+
+
+def _want_dtype(t, code, what):
+    """The library reads and writes raw memory in the descriptor's dtypes: a tensor of another
+    element size would be read or written past its end, so it is refused here."""
+    if code is not None and t.dtype != _TORCH_DTYPE[code]:
+        raise ValueError(f"{what} has dtype {t.dtype}, the call needs {_TORCH_DTYPE[code]}")
+
+
+def _dtypes(**groups):
+    """All dtype checks of a call, before anything else is looked at: each keyword is
+    `name=(dtype code, tensor or list of tensors or None)`."""
+    for what, (code, ts) in groups.items():
+        if ts is None:
+            continue
+        for t in (ts if isinstance(ts, (list, tuple)) else [ts]):
+            _want_dtype(t, code, what)
+
+
+def _panel_array(panels, rows, cols, what, dtype=None):
     """q 2-D device tensors with unit column stride and one common row stride ->
     (host array of device pointers, leading dimension in elements)."""
     ld = None
     ptrs = (ctypes.c_void_p * len(panels))()
     for t, p in enumerate(panels):
+        _want_dtype(p, dtype, f"{what}[{t}]")
         if p.dim() != 2 or tuple(p.shape) != (rows, cols):
             raise ValueError(f"{what}[{t}] has shape {tuple(p.shape)}, expected {(rows, cols)}")
         if not p.is_cuda:
@@ -248,7 +279,8 @@ def _panel_array(panels, rows, cols, what):
     return ptrs, ld
 
 
-def _out(t, rows, cols, what):
+def _out(t, rows, cols, what, dtype=None):
+    _want_dtype(t, dtype, what)
     if t.dim() != 2 or tuple(t.shape) != (rows, cols) or not t.is_cuda or (cols > 1 and t.stride(1) != 1):
         raise ValueError(f"{what}: need a device tensor of shape {(rows, cols)} with contiguous rows")
     return ctypes.c_void_p(t.data_ptr()), (t.stride(0) if rows > 1 else max(t.stride(0), cols))
@@ -262,6 +294,8 @@ def _stream(stream):
 def _ws(workspace):
     if workspace is None:
         return None, 0
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace: need a contiguous device tensor")
     return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
 
 
@@ -269,14 +303,21 @@ def linear_fwd(desc, a_panels, b_panels, bias, act, c_out, preact_out=None, work
                stream=None):
     """tess_linear_fwd: c_out = act(sum_t a_panels[t] @ b_panels[t] + bias)."""
     m, kb, n = block_shape(desc)
-    ap, lda = _panel_array(a_panels, m, kb, "a_panels")
-    bp, ldb = _panel_array(b_panels, kb, n, "b_panels")
-    cp, ldc = _out(c_out, m, n, "c_out")
+    _dtypes(a_panels=(desc.in_dtype, a_panels), b_panels=(desc.in_dtype, b_panels),
+            bias=(desc.in_dtype, bias), c_out=(desc.out_dtype, c_out),
+            preact_out=(desc.out_dtype, preact_out))
+    ap, lda = _panel_array(a_panels, m, kb, "a_panels", desc.in_dtype)
+    bp, ldb = _panel_array(b_panels, kb, n, "b_panels", desc.in_dtype)
+    cp, ldc = _out(c_out, m, n, "c_out", desc.out_dtype)
     pre = None
     if preact_out is not None:
-        pre, ldp = _out(preact_out, m, n, "preact_out")
+        pre, ldp = _out(preact_out, m, n, "preact_out", desc.out_dtype)
         if ldp != ldc:
             raise ValueError("preact_out must share c_out's leading dimension")
+    if bias is not None:
+        _want_dtype(bias, desc.in_dtype, "bias")
+        if tuple(bias.shape) != (n,) or not bias.is_cuda or not bias.is_contiguous():
+            raise ValueError(f"bias: need a contiguous device tensor of shape {(n,)}")
     bptr = ctypes.c_void_p(bias.data_ptr()) if bias is not None else None
     wsp, wsb = _ws(workspace)
     st = lib().tess_linear_fwd(ctypes.byref(desc), ap, lda, bp, ldb, bptr, act, cp, ldc, pre,
@@ -288,9 +329,11 @@ def linear_fwd(desc, a_panels, b_panels, bias, act, c_out, preact_out=None, work
 def linear_bwd_dx(desc, dy_panels, w_panels, dx_out, workspace=None, stream=None):
     """tess_linear_bwd_dx: dx_out = sum_t dy_panels[t] @ w_panels[t]^T."""
     m, kb, n = block_shape(desc)
-    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels")
-    wp, ldw = _panel_array(w_panels, kb, n, "w_panels")
-    op, ldo = _out(dx_out, m, kb, "dx_out")
+    _dtypes(dy_panels=(desc.in_dtype, dy_panels), w_panels=(desc.in_dtype, w_panels),
+            dx_out=(desc.out_dtype, dx_out))
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels", desc.in_dtype)
+    wp, ldw = _panel_array(w_panels, kb, n, "w_panels", desc.in_dtype)
+    op, ldo = _out(dx_out, m, kb, "dx_out", desc.out_dtype)
     wsp, wsb = _ws(workspace)
     st = lib().tess_linear_bwd_dx(ctypes.byref(desc), dyp, lddy, wp, ldw, op, ldo, wsp, wsb,
                                   _stream(stream))
@@ -301,10 +344,12 @@ def linear_bwd_dx(desc, dy_panels, w_panels, dx_out, workspace=None, stream=None
 def linear_bwd_dx_act(desc, dy_panels, w_panels, preact, act, dz_out, workspace=None, stream=None):
     """tess_linear_bwd_dx_act: dz_out = (sum_t dy_panels[t] @ w_panels[t]^T) * act'(preact)."""
     m, kb, n = block_shape(desc)
-    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels")
-    wp, ldw = _panel_array(w_panels, kb, n, "w_panels")
-    op, ldo = _out(dz_out, m, kb, "dz_out")
-    zp, ldz = _out(preact, m, kb, "preact") if preact is not None else (None, 0)
+    _dtypes(dy_panels=(desc.in_dtype, dy_panels), w_panels=(desc.in_dtype, w_panels),
+            preact=(desc.in_dtype, preact), dz_out=(desc.out_dtype, dz_out))
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels", desc.in_dtype)
+    wp, ldw = _panel_array(w_panels, kb, n, "w_panels", desc.in_dtype)
+    op, ldo = _out(dz_out, m, kb, "dz_out", desc.out_dtype)
+    zp, ldz = _out(preact, m, kb, "preact", desc.in_dtype) if preact is not None else (None, 0)
     wsp, wsb = _ws(workspace)
     st = lib().tess_linear_bwd_dx_act(ctypes.byref(desc), dyp, lddy, wp, ldw, zp, ldz, act, op, ldo,
                                       wsp, wsb, _stream(stream))
@@ -316,9 +361,11 @@ def linear_bwd_dw_bias(desc, x_panels, dy_panels, dw_out, dbias_out, accumulate=
                        workspace=None, stream=None):
     """tess_linear_bwd_dw_bias: linear_bwd_dw plus dbias_out (+)= column sums of the dy panels."""
     m, kb, n = block_shape(desc)
-    xp, ldx = _panel_array(x_panels, m, kb, "x_panels")
-    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels")
-    op, ldo = _out(dw_out, kb, n, "dw_out")
+    _dtypes(x_panels=(desc.in_dtype, x_panels), dy_panels=(desc.in_dtype, dy_panels),
+            dw_out=(F32 if accumulate else desc.out_dtype, dw_out))
+    xp, ldx = _panel_array(x_panels, m, kb, "x_panels", desc.in_dtype)
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels", desc.in_dtype)
+    op, ldo = _out(dw_out, kb, n, "dw_out", F32 if accumulate else desc.out_dtype)
     if dbias_out is not None and (dbias_out.dtype != torch.float32 or tuple(dbias_out.shape) != (n,)
                                   or not dbias_out.is_cuda or not dbias_out.is_contiguous()):
         raise ValueError(f"dbias_out: need a contiguous device float32 tensor of shape {(n,)}")
@@ -334,9 +381,11 @@ def linear_bwd_dx_step(desc, dy_block, w_block, partial_out, accumulate=False, w
                        stream=None):
     """tess_linear_bwd_dx_step: partial_out (fp32) (+)= dy_block @ w_block^T."""
     m, kb, n = block_shape(desc)
-    ap, lda = _out(dy_block, m, n, "dy_block")
-    bp, ldb = _out(w_block, kb, n, "w_block")
-    op, ldo = _out(partial_out, m, kb, "partial_out")
+    _dtypes(dy_block=(desc.in_dtype, dy_block), w_block=(desc.in_dtype, w_block),
+            partial_out=(F32, partial_out))
+    ap, lda = _out(dy_block, m, n, "dy_block", desc.in_dtype)
+    bp, ldb = _out(w_block, kb, n, "w_block", desc.in_dtype)
+    op, ldo = _out(partial_out, m, kb, "partial_out", F32)
     wsp, wsb = _ws(workspace)
     st = lib().tess_linear_bwd_dx_step(ctypes.byref(desc), ap, lda, bp, ldb, op, ldo,
                                        1 if accumulate else 0, wsp, wsb, _stream(stream))
@@ -348,9 +397,11 @@ def linear_bwd_dw_step(desc, x_block, dy_block, partial_out, accumulate=False, w
                        stream=None):
     """tess_linear_bwd_dw_step: partial_out (fp32) (+)= x_block^T @ dy_block."""
     m, kb, n = block_shape(desc)
-    ap, lda = _out(x_block, m, kb, "x_block")
-    bp, ldb = _out(dy_block, m, n, "dy_block")
-    op, ldo = _out(partial_out, kb, n, "partial_out")
+    _dtypes(x_block=(desc.in_dtype, x_block), dy_block=(desc.in_dtype, dy_block),
+            partial_out=(F32, partial_out))
+    ap, lda = _out(x_block, m, kb, "x_block", desc.in_dtype)
+    bp, ldb = _out(dy_block, m, n, "dy_block", desc.in_dtype)
+    op, ldo = _out(partial_out, kb, n, "partial_out", F32)
     wsp, wsb = _ws(workspace)
     st = lib().tess_linear_bwd_dw_step(ctypes.byref(desc), ap, lda, bp, ldb, op, ldo,
                                        1 if accumulate else 0, wsp, wsb, _stream(stream))
@@ -362,9 +413,11 @@ def linear_bwd_dw(desc, x_panels, dy_panels, dw_out, accumulate=False, workspace
                   stream=None):
     """tess_linear_bwd_dw: dw_out (+)= sum_t x_panels[t]^T @ dy_panels[t]."""
     m, kb, n = block_shape(desc)
-    xp, ldx = _panel_array(x_panels, m, kb, "x_panels")
-    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels")
-    op, ldo = _out(dw_out, kb, n, "dw_out")
+    _dtypes(x_panels=(desc.in_dtype, x_panels), dy_panels=(desc.in_dtype, dy_panels),
+            dw_out=(F32 if accumulate else desc.out_dtype, dw_out))
+    xp, ldx = _panel_array(x_panels, m, kb, "x_panels", desc.in_dtype)
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels", desc.in_dtype)
+    op, ldo = _out(dw_out, kb, n, "dw_out", F32 if accumulate else desc.out_dtype)
     wsp, wsb = _ws(workspace)
     st = lib().tess_linear_bwd_dw(ctypes.byref(desc), xp, ldx, dyp, lddy, op, ldo,
                                   1 if accumulate else 0, wsp, wsb, _stream(stream))

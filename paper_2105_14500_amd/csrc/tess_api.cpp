@@ -2,15 +2,20 @@
 // mapping of the three Tesseract products onto one batched-panel GEMM launch,
 // kernel/tile/split selection.  No HIP call happens before validation has passed.
 #include "tess_internal.h"
+#include "tesseract_diag.h"
 
-#include <stdlib.h>
+#include <atomic>
 
 namespace tess {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Shape-only part of the plan (what tess_linear_workspace_bytes can know).
-static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
+// Tuning overrides of the diagnostic interface (0 = the cost model decides).
+static std::atomic<int> g_force_tile{0}, g_force_splits{0};
+
+// Shape-only part of the plan (what tess_linear_workspace_bytes can know).  a_kc / b_kc:
+// operand orientation of the call (see GemmArgs).
+static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16, bool a_kc, bool b_kc)
 {
     Plan p{};
     p.path = Path::Generic;
@@ -19,6 +24,10 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
     p.direct = 0;
     p.ws_bytes = 0;
     if (!in_bf16) return p;
+    // the matrix-core path moves 16-byte granules (8 bf16) along the contiguous index of
+    // each operand: extents that are no multiple of 8 take the plain kernel
+    if (a_kc ? (Kp % 8 != 0) : (M % 8 != 0)) return p;
+    if (b_kc ? (Kp % 8 != 0) : (N % 8 != 0)) return p;
     p.path = Path::Mfma;
     const int64_t kt_total = (int64_t)q * ((Kp + BK_HOST - 1) / BK_HOST);
     p.direct = (Kp % BK_HOST == 0) ? 1 : 0;
@@ -52,9 +61,10 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
             if (cost < best) { best = cost; p.bm = p.bn = t; p.splits = sp; }
         }
     }
-    // tuning overrides, read at every call so that the workspace query and the launch agree
-    if (const char* e = getenv("TESS_SPLITS")) { const int v = atoi(e); if (v >= 1 && kt_total / v >= 1) p.splits = v; }
-    if (const char* e = getenv("TESS_TILE")) { const int v = atoi(e); if (v == 128 || (v == 256 && p.direct && M >= 256 && N >= 256)) p.bm = p.bn = v; }
+    // tuning overrides of the diagnostic interface; the workspace query, the plan query and
+    // the launch all pass through here, so they agree
+    if (const int v = g_force_splits.load(std::memory_order_relaxed)) { if (v >= 1 && kt_total / v >= 1) p.splits = v; }
+    if (const int v = g_force_tile.load(std::memory_order_relaxed)) { if (v == 128 || (v == 256 && p.direct && M >= 256 && N >= 256)) p.bm = p.bn = v; }
     const int64_t tiles = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
     if (p.splits > 1)
         p.ws_bytes = (size_t)p.splits * tiles * p.bm * p.bn * sizeof(float) +
@@ -62,25 +72,21 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16)
     return p;
 }
 
-Plan make_plan(const GemmArgs& g)
+// Plan of a launch with its operands: the shape plan, refused when the matrix-core path
+// that the shape selects cannot take these pointers or leading dimensions (a silent drop
+// to the plain kernel would be orders of magnitude slower than what tess_linear_plan says).
+static tess_status make_plan(const GemmArgs& g, Plan& p)
 {
-    Plan p = shape_plan(g.M, g.N, g.Kp, g.q, !g.in_f32);
-    if (p.path == Path::Mfma) {
-        // requirements of the 16-byte granule loaders
-        bool ok = (g.lda % 8 == 0) && (g.ldb % 8 == 0);
-        if (g.a_kc) ok = ok && (g.Kp % 8 == 0); else ok = ok && (g.M % 8 == 0) && g.M >= 8;
-        if (g.b_kc) ok = ok && (g.Kp % 8 == 0); else ok = ok && (g.N % 8 == 0) && g.N >= 8;
-        for (int t = 0; t < g.q && ok; ++t) ok = aligned16(g.a[t]) && aligned16(g.b[t]);
-        // 32-bit byte offsets inside a panel
-        const int64_t a_rows = g.a_kc ? g.M : g.Kp, b_rows = g.b_kc ? g.N : g.Kp;
-        ok = ok && (a_rows * g.lda * 2 < (int64_t)1 << 32) && (b_rows * g.ldb * 2 < (int64_t)1 << 32);
-        if (!ok) {
-            p.path = Path::Generic;
-            p.splits = 1;
-            p.ws_bytes = 0;
-        }
-    }
-    return p;
+    p = shape_plan(g.M, g.N, g.Kp, g.q, !g.in_f32, g.a_kc != 0, g.b_kc != 0);
+    if (p.path != Path::Mfma) return TESS_OK;
+    if (g.lda % 8 != 0 || g.ldb % 8 != 0) return TESS_ERR_ALIGN;
+    for (int t = 0; t < g.q; ++t)
+        if (!aligned16(g.a[t]) || !aligned16(g.b[t])) return TESS_ERR_ALIGN;
+    // 32-bit byte offsets inside a panel (the loaders add up to 4 KiB to every offset)
+    const int64_t a_rows = g.a_kc ? g.M : g.Kp, b_rows = g.b_kc ? g.N : g.Kp;
+    const int64_t lim = ((int64_t)1 << 32) - 4096;
+    if (a_rows * g.lda * 2 >= lim || b_rows * g.ldb * 2 >= lim) return TESS_ERR_UNSUPPORTED;
+    return TESS_OK;
 }
 
 static tess_status check_desc(const tess_desc* d)
@@ -110,12 +116,17 @@ static tess_status check_panels(const void* const* p, int q)
 
 static tess_status run(GemmArgs& g, void* workspace, size_t workspace_bytes, void* stream)
 {
-    const Plan p = make_plan(g);
+    Plan p;
+    const tess_status ps = make_plan(g, p);
+    if (ps != TESS_OK) return ps;
     if (p.ws_bytes > 0) {
         if (!workspace || workspace_bytes < p.ws_bytes) return TESS_ERR_WORKSPACE;
         if (reinterpret_cast<uintptr_t>(workspace) & 255u) return TESS_ERR_WORKSPACE;
         g.ws = static_cast<float*>(workspace);
     }
+#ifdef TESS_STAMPS
+    if (p.ws_bytes == 0) g.ws = static_cast<float*>(workspace);   // diagnostic build: room for the time stamps
+#endif
     g.splits = p.splits;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = (p.path == Path::Mfma) ? launch_mfma(g, p, s) : launch_generic(g, s);
@@ -148,11 +159,11 @@ size_t tess_linear_workspace_bytes(const tess_desc* desc, int op)
                   n = desc->c / desc->q;
     const bool bf = desc->in_dtype == TESS_BF16;
     switch (op) {
-        case TESS_OP_FWD: return shape_plan(m, n, kb, desc->q, bf).ws_bytes;
-        case TESS_OP_BWD_DX: return shape_plan(m, kb, n, desc->q, bf).ws_bytes;
-        case TESS_OP_BWD_DW: return shape_plan(kb, n, m, desc->q, bf).ws_bytes;
-        case TESS_OP_BWD_DX_STEP: return shape_plan(m, kb, n, 1, bf).ws_bytes;
-        case TESS_OP_BWD_DW_STEP: return shape_plan(kb, n, m, 1, bf).ws_bytes;
+        case TESS_OP_FWD: return shape_plan(m, n, kb, desc->q, bf, true, false).ws_bytes;
+        case TESS_OP_BWD_DX: return shape_plan(m, kb, n, desc->q, bf, true, true).ws_bytes;
+        case TESS_OP_BWD_DW: return shape_plan(kb, n, m, desc->q, bf, false, false).ws_bytes;
+        case TESS_OP_BWD_DX_STEP: return shape_plan(m, kb, n, 1, bf, true, true).ws_bytes;
+        case TESS_OP_BWD_DW_STEP: return shape_plan(kb, n, m, 1, bf, false, false).ws_bytes;
         default: return 0;
     }
 }
@@ -168,11 +179,11 @@ tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int
     const bool bf = desc->in_dtype == TESS_BF16;
     Plan p;
     switch (op) {
-        case TESS_OP_FWD: p = shape_plan(m, n, kb, desc->q, bf); break;
-        case TESS_OP_BWD_DX: p = shape_plan(m, kb, n, desc->q, bf); break;
-        case TESS_OP_BWD_DW: p = shape_plan(kb, n, m, desc->q, bf); break;
-        case TESS_OP_BWD_DX_STEP: p = shape_plan(m, kb, n, 1, bf); break;
-        case TESS_OP_BWD_DW_STEP: p = shape_plan(kb, n, m, 1, bf); break;
+        case TESS_OP_FWD: p = shape_plan(m, n, kb, desc->q, bf, true, false); break;
+        case TESS_OP_BWD_DX: p = shape_plan(m, kb, n, desc->q, bf, true, true); break;
+        case TESS_OP_BWD_DW: p = shape_plan(kb, n, m, desc->q, bf, false, false); break;
+        case TESS_OP_BWD_DX_STEP: p = shape_plan(m, kb, n, 1, bf, true, true); break;
+        case TESS_OP_BWD_DW_STEP: p = shape_plan(kb, n, m, 1, bf, false, false); break;
         default: return TESS_ERR_UNSUPPORTED;
     }
     *tile_m = p.bm; *tile_n = p.bn; *k_splits = p.splits;
@@ -392,13 +403,23 @@ tess_status tess_layernorm_bwd_apply(const void* xhat, int64_t ldx, const void* 
     return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
 }
 
-tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, void* hip_stream)
+tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, int32_t data,
+                                 void* hip_stream)
 {
     if (!sink) return TESS_ERR_NULL;
     if (workgroups < 1 || workgroups > 65536 || iters < 1) return TESS_ERR_SHAPE;
-    hipError_t e = launch_mfma_probe(static_cast<float*>(sink), workgroups, iters,
+    if (data != 0 && data != 1) return TESS_ERR_UNSUPPORTED;
+    hipError_t e = launch_mfma_probe(static_cast<float*>(sink), workgroups, iters, data,
                                      static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
+}
+
+tess_status tess_diag_set_plan_override(int32_t tile, int32_t k_splits)
+{
+    if ((tile != 0 && tile != 128 && tile != 256) || k_splits < 0 || k_splits > 64) return TESS_ERR_UNSUPPORTED;
+    g_force_tile.store(tile, std::memory_order_relaxed);
+    g_force_splits.store(k_splits, std::memory_order_relaxed);
+    return TESS_OK;
 }
 
 tess_status tess_tile_of_block(int32_t block, int32_t tiles_m, int32_t tiles_n, int32_t* tm,

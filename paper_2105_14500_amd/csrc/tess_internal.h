@@ -88,13 +88,10 @@ struct Plan {
     size_t ws_bytes;
 };
 
-// Chooses kernel family, tile and split for a launch; pure host arithmetic.
-Plan make_plan(const GemmArgs& g);
-
 // Enqueue; returns hipSuccess or the launch error.
 hipError_t launch_generic(const GemmArgs& g, hipStream_t s);
 hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s);
-hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, hipStream_t s);
+hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, int real_data, hipStream_t s);
 hipError_t launch_row_sums(const void* x, int64_t m, int64_t w, int64_t ldx, int in_f32,
                            int accumulate, float* out, hipStream_t s);
 hipError_t launch_row_sums_bwd(const void* xhat, const void* g, int64_t m, int64_t w, int64_t ldx,

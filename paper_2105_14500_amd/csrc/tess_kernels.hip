@@ -19,6 +19,18 @@ typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Build-time diagnostic (off in the product build): wavefront 0 of every workgroup writes
+// 100 MHz timestamps of its phases to the workspace.
+#ifdef TESS_STAMPS
+#define TESS_STAMP(i)                                                                      \
+    do {                                                                                   \
+        if (threadIdx.x == 0)                                                              \
+            ((unsigned long long*)g.ws)[(blockIdx.z * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); \
+    } while (0)
+#else
+#define TESS_STAMP(i)
+#endif
+
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 #define GLB_PTR(T) __attribute__((address_space(1))) T*
 
@@ -323,16 +335,20 @@ struct DmaLoader {
     __device__ __forceinline__ void request(IT it, const u32x4& rsrc, uint32_t lds_stage, int wave_u,
                                             uint32_t soff) const
     {
-        if constexpr (it % 4 == 0) {
-            const uint32_t m0 = lds_stage + (uint32_t)(wave_u * ITERS + it) * 1024u;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(m0) : "m0", "memory");
-        }
         // the descriptor must sit in scalar registers whatever the optimizer did to it
         u32x4 d;
         d[0] = __builtin_amdgcn_readfirstlane(rsrc[0]);
         d[1] = __builtin_amdgcn_readfirstlane(rsrc[1]);
         d[2] = __builtin_amdgcn_readfirstlane(rsrc[2]);
         d[3] = __builtin_amdgcn_readfirstlane(rsrc[3]);
+        // One M0 value serves the four requests of a group (they differ in the immediate).
+        // The compiler is only told that M0 is clobbered, not that it must survive until
+        // the group's last request, so the build scans the generated code and fails if
+        // anything but these statements writes M0 (paper_2105_14500_amd/build.py).
+        if constexpr (it % 4 == 0) {
+            const uint32_t m0 = lds_stage + (uint32_t)(wave_u * ITERS + it) * 1024u;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(m0) : "m0", "memory");
+        }
         asm volatile("buffer_load_dwordx4 %0, %1, %2 offen offset:%3 lds"
                      :
                      : "v"(off[it]), "s"(d), "s"(soff), "n"((it % 4) * 1024)
@@ -508,12 +524,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     constexpr int WTM = BM / WGM, WTN = BN / WGN;      // wave tile
     constexpr int FM = WTM / 32, FN = WTN / 32;        // 32x32 fragments per wave tile
     constexpr int KSTEPS = BK / 16;
+    constexpr bool SNAKE = true;
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static_assert(DIRECT || NSTAGE == 2, "the register-staged loader is double-buffered");
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    TESS_STAMP(0);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int wm = wave / WGN, wn = wave % WGN;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
@@ -585,8 +603,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     // is fed while the reads and requests are in flight.
     auto mfma_step = [&](auto buf, auto&& side) {
         static_for<FM * FN>([&](auto x) {
-            constexpr int i = x / FN, j = x % FN;
-            acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[x], 0, 0, 0);
+            // serpentine over the fragment grid: consecutive MFMAs share one operand
+            // register set (fewer operand-bus toggles; a few percent under the power cap)
+            constexpr int i = x / FN, j = (SNAKE && (i & 1)) ? FN - 1 - x % FN : x % FN;
+            acc[i * FN + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i * FN + j], 0, 0, 0);
             side(x);
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -630,6 +650,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
         rq_stage = __builtin_amdgcn_readfirstlane(lds_base + stage * STAGE_BYTES);
         rq_asoff = __builtin_amdgcn_readfirstlane(ld_ks * a_kstep);
         rq_bsoff = __builtin_amdgcn_readfirstlane(ld_ks * b_kstep);
+#ifdef TESS_DBG_SAMEK
+        rq_asoff = rq_bsoff = 0;
+#endif
         const int t = ld_t < g.q ? ld_t : g.q - 1;
         rq_rsrc_a = LA::descriptor(ka->a[t]);
         rq_rsrc_b = LB::descriptor(ka->b[t]);
@@ -644,8 +667,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     constexpr int STRIDE = RQ_SPAN / LOADS;
     static_assert(STRIDE >= 1, "requests spaced evenly over the MFMA slots");
     auto request_at = [&](auto slot) {
+#ifndef TESS_DBG_NOLOAD
         if constexpr (slot % STRIDE == 0 && slot / STRIDE < LOADS)
             request(std::integral_constant<int, slot / STRIDE>{});
+#endif
     };
     // The k16 steps 0 .. KSTEPS-2 of the tile in `stage`: each fetches the next step's
     // fragments with its first MFMAs.  REQ: also carry requests (slots FM*FN ..).
@@ -692,6 +717,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             static_for<FIRST>([&](auto it) { request(it); });
             wait_vmcnt<(NSTAGE - 2) * LOADS + FIRST>();            // tile 0 has landed
             lds_barrier();
+            TESS_STAMP(1);
             load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
         }
         int stage = 0;
@@ -705,10 +731,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             last_step(next, yes, yes);
             stage = next;
         }
+        TESS_STAMP(2);
         // the epilogue reuses the LDS: nothing may still be landing in it
         wait_vmcnt<0>();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         lds_barrier();
+        TESS_STAMP(3);
     } else {
         // register-staged double buffer with a zero-filled K tail
         SA sa_;
@@ -768,6 +796,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             static_for<16>([&](auto r) { w[(f * 16 + r) * 64] = acc[f][r()]; });
             __builtin_amdgcn_sched_barrier(0);
         });
+#ifdef TESS_STAMPS
+        TESS_STAMP(5); wait_vmcnt<0>(); TESS_STAMP(6);
+#endif
         return;
     }
     // The wavefront passes its accumulators through a private slice of the (now idle)
@@ -859,6 +890,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             else if (g.act == TESS_ACT_GELU_ERF) drain(std::integral_constant<int, MODE_BF16_GELU>{});
             else drain(std::integral_constant<int, MODE_BF16>{});
             __builtin_amdgcn_sched_barrier(0);
+#ifdef TESS_STAMPS
+            if constexpr (half == 0) { TESS_STAMP(4); }
+            else { TESS_STAMP(5); wait_vmcnt<0>(); TESS_STAMP(6); }
+#endif
         });
     }
 }
@@ -924,8 +959,8 @@ template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool 
           bool COLSUM = false>
 static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
-    constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
     constexpr int NT = 64 * WGM * WGN;
+    constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
     auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT, COLSUM>;
     // the dynamic LDS limit is a per-device attribute of the kernel: set it once per device
     // (a bit per device id; setting it twice from two threads is harmless)
@@ -966,30 +1001,48 @@ static hipError_t launch_layout(const GemmArgs& g, const Plan& p, hipStream_t s)
     return hipErrorInvalidValue;
 }
 
-// Register-resident MFMA loop: 8 independent accumulator chains per wavefront.
+// Register-resident MFMA loop: the 4 x 4 grid of accumulator tiles of the GEMM kernel fed
+// from four A and four B fragments that stay in registers.  REAL: fragments hold values
+// distributed like the workloads' operands (a hash of the lane id shaped into a rough
+// bell curve: N(0,1) for A, N(0,0.02) for B) instead of small integers; on this hardware
+// the sustained clock under the board power limit depends on how much the operands switch.
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ float probe_bell(uint32_t seed)
+{
+    float a = 0.0f;
+    for (int i = 0; i < 4; ++i) { seed = probe_hash(seed + 977u * i); a += (float)(seed & 0xffffu) * (1.0f / 65536.0f); }
+    return (a - 2.0f) * 1.7320508f;        // sum of four uniforms: mean 2, variance 1/3
+}
+template <bool REAL>
 __global__ __launch_bounds__(256) void tess_mfma_probe_kernel(float* sink, int iters)
 {
-    bf16x8 a, b;
-    for (int e = 0; e < 8; ++e) {
-        a[e] = (__bf16)(float)((threadIdx.x + e) % 7 - 3);
-        b[e] = (__bf16)(float)((threadIdx.x * 3 + e) % 5 - 2);
-    }
-    floatx16 c[8];
-    for (int i = 0; i < 8; ++i)
-        for (int r = 0; r < 16; ++r) c[i][r] = 0.0f;
+    bf16x8 a[4], b[4];
+    for (int f = 0; f < 4; ++f)
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t id = (blockIdx.x * 256u + threadIdx.x) * 64u + f * 8u + e;
+            a[f][e] = (__bf16)(REAL ? probe_bell(id) : (float)((int)((threadIdx.x + e + f) % 7) - 3));
+            b[f][e] = (__bf16)(REAL ? 0.02f * probe_bell(id + 0x9e3779b9u) : (float)((int)((threadIdx.x * 3 + e + f) % 5) - 2));
+        }
+    floatx16 c[16];
+    static_for<16>([&](auto x) { static_for<16>([&](auto r) { c[x][r()] = 0.0f; }); });
     for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[i], 0, 0, 0);
+        static_for<16>([&](auto x) {
+            c[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x / 4], b[x % 4], c[x], 0, 0, 0);
+        });
     }
     float sum = 0.0f;
-    for (int i = 0; i < 8; ++i)
-        for (int r = 0; r < 16; ++r) sum += c[i][r];
+    static_for<16>([&](auto x) { static_for<16>([&](auto r) { sum += c[x][r()]; }); });
     sink[blockIdx.x * 256 + threadIdx.x] = sum;
 }
 
-hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, hipStream_t s)
+hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, int real_data, hipStream_t s)
 {
-    hipLaunchKernelGGL(tess_mfma_probe_kernel, dim3(workgroups), dim3(256), 0, s, sink, iters);
+    if (real_data) hipLaunchKernelGGL(tess_mfma_probe_kernel<true>, dim3(workgroups), dim3(256), 0, s, sink, iters);
+    else hipLaunchKernelGGL(tess_mfma_probe_kernel<false>, dim3(workgroups), dim3(256), 0, s, sink, iters);
     return hipGetLastError();
 }
 

@@ -184,10 +184,12 @@ def test_empty_and_error_paths_leave_outputs_untouched():
 def test_mfma_rate_probe_runs():
     """The measurement loop launches, fills its sink and reports its flop count."""
     sink = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda:0")
-    flop = B.probe_mfma_rate(sink, 8, 10)
-    torch.cuda.synchronize()
-    assert flop == 8 * 4 * 10 * 8 * 32768.0
-    assert torch.isfinite(sink).all()
+    for real in (False, True):
+        sink.fill_(float("nan"))
+        flop = B.probe_mfma_rate(sink, 8, 10, real_data=real)
+        torch.cuda.synchronize()
+        assert flop == 8 * 4 * 10 * 16 * 32768.0
+        assert torch.isfinite(sink).all()
 
 
 def test_calls_can_be_recorded_into_a_hip_graph():

@@ -319,6 +319,51 @@ def test_gelu_identities():
     assert abs(orc.gelu_tanh(1.0) - want) < 1e-15
 
 
+def test_gelu_tanh_form_against_library_routine_and_its_gap_to_the_exact_form():
+    """The tanh form is pinned to things other than its own formula: (1) PyTorch's CPU
+    fp64 `gelu(approximate="tanh")`, a library routine; (2) the largest distance between
+    the tanh form and the exact form x Phi(x) (itself pinned by the normal-CDF table) over
+    [-8, 8]: 4.732e-4, reached at |x| = 2.699 -- a mistyped cubic coefficient moves it well
+    outside the band (0.04715 gives 1.5e-3, 0.045 gives 5.6e-4), a low digit of sqrt(2/pi)
+    moves it too; (3) the tails: identity for large x, zero for very negative x."""
+    torch = pytest.importorskip("torch")
+    xs = np.linspace(-8.0, 8.0, 160001)
+    got = np.array([orc.gelu_tanh(float(x)) for x in xs[::40]])
+    lib = torch.nn.functional.gelu(torch.from_numpy(xs[::40].copy()), approximate="tanh").numpy()
+    assert np.max(np.abs(got - lib)) < 2e-14
+    gt = np.array([orc.gelu_tanh(float(x)) for x in xs])
+    ge = np.array([orc.gelu_erf(float(x)) for x in xs])
+    gap = np.abs(gt - ge)
+    i = int(np.argmax(gap))
+    assert abs(gap[i] - 4.732e-4) < 2e-6, gap[i]
+    assert abs(abs(xs[i]) - 2.699) < 0.01, xs[i]
+    assert orc.gelu_tanh(9.0) == 9.0 and abs(orc.gelu_tanh(-9.0)) < 1e-30
+    assert abs(orc.gelu_tanh(40.0) - 40.0) == 0.0 and orc.gelu_tanh(-40.0) == 0.0
+
+
+def test_gelu_tanh_derivative_against_autograd_and_its_gap_to_the_exact_derivative():
+    """Same for the derivative: PyTorch's fp64 autograd through its own tanh-form GELU,
+    and the largest distance to the exact derivative Phi(x) + x phi(x) (pinned above by
+    tabulated values): 8.685e-4 at |x| = 2.019."""
+    torch = pytest.importorskip("torch")
+    xs = np.linspace(-8.0, 8.0, 160001)
+    xt = torch.from_numpy(xs[::40].copy()).requires_grad_()
+    torch.nn.functional.gelu(xt, approximate="tanh").sum().backward()
+    got = np.array([float(orc.gelu_tanh_grad(float(x))) for x in xs[::40]])
+    assert np.max(np.abs(got - xt.grad.numpy())) < 2e-14
+    xe = torch.from_numpy(xs[::40].copy()).requires_grad_()
+    torch.nn.functional.gelu(xe).sum().backward()
+    gote = np.array([float(orc.gelu_erf_grad(float(x))) for x in xs[::40]])
+    assert np.max(np.abs(gote - xe.grad.numpy())) < 2e-14
+    dt = np.array([float(orc.gelu_tanh_grad(float(x))) for x in xs])
+    de = np.array([float(orc.gelu_erf_grad(float(x))) for x in xs])
+    gap = np.abs(dt - de)
+    i = int(np.argmax(gap))
+    assert abs(gap[i] - 8.685e-4) < 2e-6, gap[i]
+    assert abs(abs(xs[i]) - 2.019) < 0.01, xs[i]
+    assert float(orc.gelu_tanh_grad(9.0)) == 1.0 and abs(float(orc.gelu_tanh_grad(-9.0))) < 1e-30
+
+
 def test_bf16_rounding_bit_patterns():
     def f(bits):
         return np.array([bits], dtype=np.uint32).view(np.float32)[0]
