@@ -211,8 +211,12 @@ size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
 
 /* Launch shape that the call `op` would use for this descriptor: output macro tile and
  * number of K splits (1 = the whole q-step sum stays in one workgroup's registers; > 1 =
- * partial sums go through the workspace and are summed in ascending split order before
- * the epilogue).  tile 0 x 0 means the plain fp32 kernel: fp32 inputs, or a bf16 block
+ * that many equal parts of the K range, partial sums go through the workspace and are
+ * summed in ascending order before the epilogue; 0 = the two-level schedule, which only the
+ * diagnostic override selects: one workgroup per compute unit, every tile's K range cut
+ * into a main part and a tail, the tile completed by the last of its contributors to
+ * finish, again in ascending K order).
+ * tile 0 x 0 means the plain fp32 kernel: fp32 inputs, or a bf16 block
  * whose contiguous extents are no multiple of 8.  Pure host arithmetic.  A call whose
  * plan uses the matrix cores needs 16-byte aligned panel pointers and leading dimensions
  * that are multiples of 8 elements, and returns TESS_ERR_ALIGN otherwise (it never drops

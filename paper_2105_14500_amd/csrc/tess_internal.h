@@ -46,23 +46,35 @@ struct GemmArgs {
     // followed by splits x N partial column sums
     int32_t splits;
     float* ws;
+    // two-level schedule of the STREAMK kernels (256 workgroups, see tess_mfma_kernel): the
+    // first sk_main K stages of a tile belong to its main workgroup, the rest to the tail
+    // workgroups of the tile's XCD.  ws then holds 64 partial slots per XCD, sk_flags one
+    // word per slot, sk_ctrl one word per tile.
+    int32_t sk_main;
+    unsigned long long sk_token;     // tag of this call's control words (48 bits, non-zero)
+    unsigned long long* sk_ctrl;
+    unsigned long long* sk_flags;
+    unsigned long long* stamps;      // diagnostic builds only (TESS_STAMPS): 16 time stamps per workgroup
 };
 
-// Block -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each with its
-// own L2: the block ids that land on one XCD are relabelled to a contiguous run of tile
-// ids, and tile ids walk bands of GM tile rows column by column, so that the tiles an XCD
-// has in flight form a compact patch that shares row and column panels in its L2.  GM is
-// the band height (1..8) that needs the fewest panels, GM + c / GM for the c <= 32 tiles an
-// XCD runs at a time, preferring heights that divide the grid: 8 x 4 for 32 tiles (12
-// panels), 4 x 2 for 8 (6 panels where an 8 x 1 strip needs 9).  A bijection from
-// [0, tiles_m*tiles_n) onto the tile grid for every grid size.
-__host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Position of block
+// `bid` in an order that lists XCD 0's blocks first, then XCD 1's, ...: blocks that run on
+// one XCD get a contiguous run of indices.  A bijection on [0, n).
+__host__ __device__ inline int xcd_major_index(int bid, int n)
 {
-    const int nb = tiles_m * tiles_n;
-    const int per = nb >> 3, rem = nb & 7;
+    const int per = n >> 3, rem = n & 7;
     const int xcd = bid & 7, idx = bid >> 3;
-    const int lid = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
-    const int conc = per >= 32 ? 32 : (per >= 1 ? per : 1);   // tiles of one XCD in flight
+    return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+}
+
+// Index in the tile order -> output tile.  The order walks bands of GM tile rows column by
+// column, so that a run of `conc` consecutive indices (the tiles one XCD has in flight) is a
+// compact patch that shares row and column panels in that XCD's L2.  GM is the band height
+// (1..8) that needs the fewest panels, GM + conc / GM, preferring heights that divide the
+// grid: 8 x 4 for 32 tiles (12 panels), 4 x 2 for 8 (6 panels where an 8 x 1 strip needs 9).
+// A bijection from [0, tiles_m*tiles_n) onto the tile grid for every grid size.
+__host__ __device__ inline void tile_of_index(int lid, int tiles_m, int tiles_n, int conc, int& tm, int& tn)
+{
     int GM = 1, best = 1 << 30;
     for (int gm = 1; gm <= 8 && gm <= tiles_m; ++gm) {
         // panels x gm, so that the comparison stays in integers; ragged bands cost one more
@@ -77,16 +89,35 @@ __host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = in_band / rows;
 }
 
+// Block -> output tile of a launch with one workgroup per tile: the block ids that land on
+// one XCD are relabelled to a contiguous run of tile indices (at most 32 of them in flight).
+__host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
+{
+    const int nb = tiles_m * tiles_n;
+    const int per = nb >> 3;
+    const int conc = per >= 32 ? 32 : (per >= 1 ? per : 1);   // tiles of one XCD in flight
+    tile_of_index(xcd_major_index(bid, nb), tiles_m, tiles_n, conc, tm, tn);
+}
+
 // Kernel families.
 enum class Path : int32_t { Generic = 0, Mfma = 1 };
 
 struct Plan {
     Path path;
     int32_t bm, bn;     // macro tile of the MFMA path
-    int32_t splits;     // K splits (1 = none)
+    int32_t splits;     // K splits (1 = none): equal parts over gridDim.z + reduction kernel
     int32_t direct;     // 1: global->LDS direct loads (needs Kp % 64 == 0)
+    int32_t sk_workers; // > 0: two-level (main + tails) schedule with this many workgroups (256) ...
+    int32_t sk_main;    // ... and this many K stages of every tile done by its main workgroup
     size_t ws_bytes;
 };
+
+// Workspace layout of the two-level schedule: control words (one per tile), flags (one per
+// partial slot), both 8 bytes, padded to 256 bytes; then 64 partial slots per XCD, each a
+// BM x BN fp32 tile in row order + 1 KiB of partial column sums.
+constexpr int kSkSlots = 8 * 64;
+inline size_t sk_slot_bytes(int bm, int bn) { return (size_t)bm * bn * 4 + 1024; }
+inline size_t sk_head_bytes(int64_t tiles) { return ((size_t)(tiles + kSkSlots) * 8 + 255) & ~(size_t)255; }
 
 // Enqueue; returns hipSuccess or the launch error.
 hipError_t launch_generic(const GemmArgs& g, hipStream_t s);

@@ -25,7 +25,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define TESS_STAMP(i)                                                                      \
     do {                                                                                   \
         if (threadIdx.x == 0)                                                              \
-            ((unsigned long long*)g.ws)[(blockIdx.z * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); \
+            g.stamps[(blockIdx.z * gridDim.x + blockIdx.x) * 16 + (i)] = wall_clock64(); \
     } while (0)
 #else
 #define TESS_STAMP(i)
@@ -346,12 +346,12 @@ struct DmaLoader {
         // the group's last request, so the build scans the generated code and fails if
         // anything but these statements writes M0 (paper_2105_14500_amd/build.py).
         if constexpr (it % 4 == 0) {
-            const uint32_t m0 = lds_stage + (uint32_t)(wave_u * ITERS + it) * 1024u;
+            const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_stage + (uint32_t)(wave_u * ITERS + it) * 1024u);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(m0) : "m0", "memory");
         }
         asm volatile("buffer_load_dwordx4 %0, %1, %2 offen offset:%3 lds"
                      :
-                     : "v"(off[it]), "s"(d), "s"(soff), "n"((it % 4) * 1024)
+                     : "v"(off[it]), "s"(d), "s"(__builtin_amdgcn_readfirstlane(soff)), "n"((it % 4) * 1024)
                      : "memory");
     }
 };
@@ -516,8 +516,11 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
 // fp32 accumulation, issued in the shadow of the MFMAs.  (An extra MFMA with an all-ones
 // A fragment would need accumulator registers that the tile already uses up: the
 // compiler then copies 16 registers in and out around every such MFMA.)
+// STREAMK: the workgroup walks a list of segments (see below) and fixes shared tiles up
+// through the workspace; compiled as kernels of their own so that the one-tile-per-workgroup
+// kernels keep their register allocation (the segment loop costs spills outside the K loop).
 template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT,
-          bool COLSUM = false>
+          bool COLSUM = false, bool STREAMK = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
 {
     constexpr int NT = 64 * WGM * WGN;
@@ -536,21 +539,45 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     const int wm = wave / WGN, wn = wave % WGN;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int nb = tiles_m * tiles_n;
-    int tm, tn;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
-    const int row0 = tm * BM, col0 = tn * BN;
-
-    // ---- K range of this block (split over gridDim.z in whole stages)
     const int kt_per_panel = (g.Kp + BK - 1) / BK;
     const int kt_total = g.q * kt_per_panel;
-    int kt_begin = 0, kt_end = kt_total;
-    if (g.splits > 1) {
-        const int z = blockIdx.z;
-        const int base = kt_total / g.splits, extra = kt_total % g.splits;
-        kt_begin = z * base + (z < extra ? z : extra);
-        kt_end = kt_begin + base + (z < extra ? 1 : 0);
+
+    // ---- work of this workgroup: a list of segments (output tile, range of K stages).
+    // One tile per workgroup, whole K or one of gridDim.z equal parts of it; or the
+    // two-level schedule (STREAMK) for tile counts between half and all of the compute
+    // units, one workgroup per compute unit: on every XCD (32 workgroups, n_x tiles that
+    // are consecutive in the tile order) n_x "main" workgroups take the first g.sk_main
+    // stages of one tile each, in step with each other so that they share panels in the
+    // L2 as the one-tile-per-workgroup launch does, and the remaining 32 - n_x workgroups
+    // share the tiles' remaining stages ("tails") as one sequence of (tile, stage) units.
+    // A tile is completed by whichever of its contributors finishes last (see below).
+    constexpr bool streamk = STREAMK;
+    int sk_xcd = 0, sk_i = 0, sk_nx = 0, sk_first = 0;   // XCD, index on it, its tiles: count and first
+    int sk_upw = 0, sk_L = 0;                             // tail units per tail workgroup, tail length
+    int sk_u = 0, sk_uend = 0;                            // units still to do (tail workgroups)
+    bool sk_main_todo = false;
+    if constexpr (STREAMK) {
+        sk_xcd = blockIdx.x & 7;
+        sk_i = blockIdx.x >> 3;
+        const int per = nb >> 3, rem = nb & 7;
+        sk_nx = per + (sk_xcd < rem ? 1 : 0);
+        sk_first = sk_xcd * per + (sk_xcd < rem ? sk_xcd : rem);
+        sk_L = kt_total - g.sk_main;
+        const int tails = 32 - sk_nx;
+        sk_upw = (sk_nx * sk_L + tails - 1) / tails;
+        if (sk_i < sk_nx) {
+            sk_main_todo = true;
+        } else {
+            sk_u = (sk_i - sk_nx) * sk_upw;
+            sk_uend = sk_u + sk_upw < sk_nx * sk_L ? sk_u + sk_upw : sk_nx * sk_L;
+        }
     }
-    const int nkt = kt_end - kt_begin;
+    // the segment being computed
+    int tm = 0, tn = 0, row0 = 0, col0 = 0, kt_begin = 0, nkt = 0;
+    int sk_tl = 0;                  // the tile's index among its XCD's tiles
+#ifdef TESS_STAMPS
+    int seg = -1;
+#endif
 
     typedef DmaLoader<BM, BK, A_KC, NT> LA;
     typedef DmaLoader<BN, BK, B_KC, NT> LB;
@@ -563,15 +590,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     rb.init(lane, wn * WTN);
 
     floatx16 acc[FM * FN];
-    static_for<FM * FN>([&](auto f) {
-        static_for<16>([&](auto r) { acc[f][r()] = 0.0f; });
-    });
-    // column sums (COLSUM only)
-    const bool cs_wave = COLSUM && __builtin_amdgcn_readfirstlane((int)(g.colsum != nullptr && tm == 0 && wm == 0));
+    // column sums (COLSUM only): the wavefronts that hold the top wave tile of the first tile row
+    bool cs_wave = false;
     float cs[COLSUM ? FN : 1];
-    if constexpr (COLSUM) {
-        static_for<FN>([&](auto j) { cs[j] = 0.0f; });
-    }
 
     // byte advance of one stage along K for each operand
     const uint32_t a_kstep = A_KC ? (uint32_t)BK * 2 : (uint32_t)(BK * g.lda * 2);
@@ -583,7 +604,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     typedef __attribute__((address_space(4))) const GemmArgs* KernArgs;
     const KernArgs ka = (KernArgs)__builtin_amdgcn_kernarg_segment_ptr();
     // (panel, stage-in-panel) of the next stage to fetch, advanced incrementally
-    int ld_t = kt_begin / kt_per_panel, ld_ks = kt_begin - ld_t * kt_per_panel;
+    int ld_t = 0, ld_ks = 0;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
 
     bf16x8 af[2][FM], bfr[2][FN];
@@ -638,7 +659,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     uint32_t rq_stage = 0;          // LDS address of the stage being filled
     uint32_t rq_asoff = 0, rq_bsoff = 0;   // K advance of that tile inside its panels
     u32x4 rq_rsrc_a = {0u, 0u, 0u, 0u}, rq_rsrc_b = {0u, 0u, 0u, 0u};
-    int rq_left = nkt;              // tiles not yet aimed at
+    int rq_left = 0;                // tiles not yet aimed at
     auto request = [&](auto it) {
         if constexpr (it < LA::ITERS) la.request(it, rq_rsrc_a, rq_stage, wave_u, rq_asoff);
         else lb.request(std::integral_constant<int, it - LA::ITERS>{}, rq_rsrc_b, rq_stage + A_BYTES, wave_u, rq_bsoff);
@@ -697,204 +718,420 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
 
-    if constexpr (DIRECT) {
-        // Ring of NSTAGE LDS slots; tile r lives in slot r % NSTAGE.  Barrier r (every
-        // wave has read tile r, tile r+1 has landed) frees slot r % NSTAGE; tile
-        // r+NSTAGE is then requested into it, its requests attached to the MFMAs that
-        // follow (the last k16 step of tile r, then the first steps of tile r+1).  One
-        // loop body serves the whole K range: see aim() for the tail.
-        la.init(lane, wave_u, row0, g.M, g.lda);
-        lb.init(lane, wave_u, col0, g.N, g.ldb);
-        constexpr int FIRST = (FM * FN + STRIDE - 1) / STRIDE < LOADS ? (FM * FN + STRIDE - 1) / STRIDE : LOADS;
-        if (nkt > 0) {
-            // tiles 0 .. NSTAGE-2 in bulk, and of tile NSTAGE-1 the requests that the
-            // last k16 step of a period would carry; the first body steps bring the rest
-            static_for<NSTAGE - 1>([&](auto s) {
-                aim(s);
-                static_for<LOADS>([&](auto it) { request(it); });
-            });
-            aim(NSTAGE - 1);
-            static_for<FIRST>([&](auto it) { request(it); });
-            wait_vmcnt<(NSTAGE - 2) * LOADS + FIRST>();            // tile 0 has landed
-            lds_barrier();
-            TESS_STAMP(1);
-            load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
+    for (;;) {
+        // ---- next segment
+        if constexpr (STREAMK) {
+            if (sk_main_todo) {
+                sk_main_todo = false;
+                sk_tl = sk_i;
+                kt_begin = 0;
+                nkt = g.sk_main;
+            } else {
+                if (sk_u >= sk_uend) break;
+                sk_tl = sk_u / sk_L;
+                const int at = sk_u - sk_tl * sk_L;
+                kt_begin = g.sk_main + at;
+                nkt = sk_uend - sk_u < sk_L - at ? sk_uend - sk_u : sk_L - at;
+                sk_u += nkt;
+            }
+            tile_of_index(sk_first + sk_tl, tiles_m, tiles_n, nb >> 3, tm, tn);
+        } else {
+            tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
+            kt_begin = 0;
+            nkt = kt_total;
+            if (g.splits > 1) {
+                const int z = blockIdx.z;
+                const int base = kt_total / g.splits, extra = kt_total % g.splits;
+                kt_begin = z * base + (z < extra ? z : extra);
+                nkt = base + (z < extra ? 1 : 0);
+            }
         }
-        int stage = 0;
-        for (int r = 0; r < nkt; ++r) {
-            body_steps(stage, yes);
-            const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of tile r are done
-            wait_vmcnt<(NSTAGE - 2) * LOADS>();                    // tile r+1 has landed
-            lds_barrier();                                         // barrier r
-            aim(stage);
-            last_step(next, yes, yes);
-            stage = next;
-        }
-        TESS_STAMP(2);
-        // the epilogue reuses the LDS: nothing may still be landing in it
-        wait_vmcnt<0>();
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        lds_barrier();
-        TESS_STAMP(3);
-    } else {
-        // register-staged double buffer with a zero-filled K tail
-        SA sa_;
-        SB sb_;
-        sa_.init(tid, row0, g.M, g.lda);
-        sb_.init(tid, col0, g.N, g.ldb);
-        auto fetch = [&]() {
-            const int t = ld_t < g.q ? ld_t : g.q - 1;
-            const int krem = g.Kp - ld_ks * BK;
-            sa_.fetch((const char*)ka->a[t] + (size_t)ld_ks * a_kstep, krem);
-            sb_.fetch((const char*)ka->b[t] + (size_t)ld_ks * b_kstep, krem);
-            if (++ld_ks == kt_per_panel) { ld_ks = 0; ++ld_t; }
-        };
-        auto commit = [&](int stage) {
-            char* st = lds + stage * STAGE_BYTES;
-            sa_.commit(st, tid);
-            sb_.commit(st + A_BYTES, tid);
-        };
-        if (nkt > 0) {
-            fetch();
-            commit(0);
-            __syncthreads();
-        }
-        for (int r = 0; r < nkt; ++r) {
-            const int cur = r & 1;
-            const bool more = r + 1 < nkt;
-            if (more) fetch();
-            load_frags(std::integral_constant<int, 0>{}, cur, std::integral_constant<int, 0>{});
-            body_steps(cur, no);
-            last_step(cur, no, no);
-            if (more) commit(cur ^ 1);
-            __syncthreads();
-        }
-    }
-
-    // ---- epilogue
-    if constexpr (COLSUM) {
-        // lane l holds column l % 32 of each fragment for the k-values 8 (l / 32) .. + 7 of
-        // every k16 step: the two halves of the wavefront add up to the column sum
-        if (cs_wave) {
-            float* part = g.ws + (size_t)g.splits * nb * (BM * BN) + (size_t)blockIdx.z * g.N;
-            static_for<FN>([&](auto j) {
-                const float v = cs[j] + __shfl_xor(cs[j], 32, 64);
-                const int col = col0 + wn * WTN + j * 32 + lane;
-                if (lane < 32 && col < g.N) {
-                    if (g.splits > 1) part[col] = v;
-                    else g.colsum[col] = g.accumulate ? g.colsum[col] + v : v;
-                }
-            });
-        }
-    }
-    if (g.splits > 1) {
-        // partial sums in accumulator order: [(z*nb + tile)][wave][frag][reg][lane]
-        float* w = g.ws + ((size_t)blockIdx.z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
-                   (size_t)wave * (FM * FN * 16 * 64) + lane;
-        static_for<FM * FN>([&](auto f) {
-            static_for<16>([&](auto r) { w[(f * 16 + r) * 64] = acc[f][r()]; });
-            __builtin_amdgcn_sched_barrier(0);
-        });
 #ifdef TESS_STAMPS
-        TESS_STAMP(5); wait_vmcnt<0>(); TESS_STAMP(6);
+        ++seg;
 #endif
-        return;
-    }
-    // The wavefront passes its accumulators through a private slice of the (now idle)
-    // LDS, half of its tile at a time, to turn the MFMA fragment layout into rows: a
-    // short rolled loop then handles four adjacent columns per lane, so every output
-    // row leaves as one contiguous run and the code stays small.
-    {
-        constexpr int HR = WTM / 2;                    // rows per half
-        constexpr int ROWB = WTN * 4;                  // fp32 bytes per row of the wave tile
-        constexpr int CPR = WTN / 4;                   // 16-byte chunks per row
-        constexpr int RPI = 64 / CPR;                  // rows per 64-lane pass
-        static_assert(FM % 2 == 0, "two halves of whole fragments");
-        static_assert(NSTAGE * STAGE_BYTES >= WGM * WGN * HR * ROWB, "LDS holds half a tile in fp32");
-        char* slice = lds + wave * (HR * ROWB);
-        const int esize = g.out_f32 ? 4 : 2;
-        const bool vec = ((g.ldo * esize) % 16 == 0) &&
-                         ((reinterpret_cast<uintptr_t>(g.out) & 15u) == 0) &&
-                         (!g.preact || (reinterpret_cast<uintptr_t>(g.preact) & 15u) == 0) &&
-                         (!g.zin || (((reinterpret_cast<uintptr_t>(g.zin) & 7u) == 0) && (g.ldz % 4 == 0)));
-        // chunk c of row r is kept at chunk c ^ (8 * bit 2 of r): the two half-waves of
-        // a fragment (rows r and r+4) then write to different banks
-        constexpr int NIT = HR / RPI;                  // passes of the drain loop per half
-        // dX through GELU': the pre-activations are fetched before the accumulators are staged,
-        // so that their latency is hidden behind the LDS traffic instead of sitting in the loop
-        const bool dgelu = g.zin && g.dact == TESS_ACT_GELU_ERF && !g.out_f32 && !g.in_f32 &&
-                           !g.preact && g.act == TESS_ACT_NONE;
-        static_for<2>([&](auto half) {
-            const int wrow0 = row0 + wm * WTM + half * HR, wcol0 = col0 + wn * WTN;
-            // a lane serves the same four columns in every pass
-            const int c = lane % CPR, col = wcol0 + c * 4;
-            u32x2 zr[NIT];
-            if (dgelu) {
-                static_for<NIT>([&](auto it) {
-                    const int row = wrow0 + it * RPI + lane / CPR;
-                    zr[it] = u32x2{0u, 0u};
-                    if (row < g.M && col < g.N) {
-                        const uint16_t* zp = (const uint16_t*)g.zin + (int64_t)row * g.ldz + col;
-                        if (vec && col + 3 < g.N) {
-                            zr[it] = *(const u32x2*)zp;
-                        } else {
-                            for (int e = 0; e < 4; ++e)
-                                if (col + e < g.N) zr[it][e >> 1] |= (uint32_t)zp[e] << (16 * (e & 1));
+        row0 = tm * BM;
+        col0 = tn * BN;
+        ld_t = kt_begin / kt_per_panel;
+        ld_ks = kt_begin - ld_t * kt_per_panel;
+        static_for<FM * FN>([&](auto f) {
+            static_for<16>([&](auto r) { acc[f][r()] = 0.0f; });
+        });
+        if constexpr (COLSUM) {
+            cs_wave = __builtin_amdgcn_readfirstlane((int)(g.colsum != nullptr && tm == 0 && wm == 0));
+            static_for<FN>([&](auto j) { cs[j] = 0.0f; });
+        }
+
+        if constexpr (DIRECT) {
+            // Ring of NSTAGE LDS slots; tile r lives in slot r % NSTAGE.  Barrier r (every
+            // wave has read tile r, tile r+1 has landed) frees slot r % NSTAGE; tile
+            // r+NSTAGE is then requested into it, its requests attached to the MFMAs that
+            // follow (the last k16 step of tile r, then the first steps of tile r+1).  One
+            // loop body serves the whole K range: see aim() for the tail.
+            la.init(lane, wave_u, row0, g.M, g.lda);
+            lb.init(lane, wave_u, col0, g.N, g.ldb);
+            rq_left = nkt;
+            constexpr int FIRST = (FM * FN + STRIDE - 1) / STRIDE < LOADS ? (FM * FN + STRIDE - 1) / STRIDE : LOADS;
+            if (nkt > 0) {
+                // tiles 0 .. NSTAGE-2 in bulk, and of tile NSTAGE-1 the requests that the
+                // last k16 step of a period would carry; the first body steps bring the rest
+                static_for<NSTAGE - 1>([&](auto s) {
+                    aim(s);
+                    static_for<LOADS>([&](auto it) { request(it); });
+                });
+                aim(NSTAGE - 1);
+                static_for<FIRST>([&](auto it) { request(it); });
+                wait_vmcnt<(NSTAGE - 2) * LOADS + FIRST>();            // tile 0 has landed
+                lds_barrier();
+                TESS_STAMP(1 + 4 * seg);
+                load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
+            }
+            int stage = 0;
+            for (int r = 0; r < nkt; ++r) {
+                body_steps(stage, yes);
+                const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // my reads of tile r are done
+                wait_vmcnt<(NSTAGE - 2) * LOADS>();                    // tile r+1 has landed
+                lds_barrier();                                         // barrier r
+                aim(stage);
+                last_step(next, yes, yes);
+                stage = next;
+            }
+            TESS_STAMP(2 + 4 * seg);
+            // the epilogue reuses the LDS: nothing may still be landing in it
+            wait_vmcnt<0>();
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            lds_barrier();
+        } else {
+            // register-staged double buffer with a zero-filled K tail
+            SA sa_;
+            SB sb_;
+            sa_.init(tid, row0, g.M, g.lda);
+            sb_.init(tid, col0, g.N, g.ldb);
+            auto fetch = [&]() {
+                const int t = ld_t < g.q ? ld_t : g.q - 1;
+                const int krem = g.Kp - ld_ks * BK;
+                sa_.fetch((const char*)ka->a[t] + (size_t)ld_ks * a_kstep, krem);
+                sb_.fetch((const char*)ka->b[t] + (size_t)ld_ks * b_kstep, krem);
+                if (++ld_ks == kt_per_panel) { ld_ks = 0; ++ld_t; }
+            };
+            auto commit = [&](int stage) {
+                char* st = lds + stage * STAGE_BYTES;
+                sa_.commit(st, tid);
+                sb_.commit(st + A_BYTES, tid);
+            };
+            if (nkt > 0) {
+                fetch();
+                commit(0);
+                __syncthreads();
+            }
+            for (int r = 0; r < nkt; ++r) {
+                const int cur = r & 1;
+                const bool more = r + 1 < nkt;
+                if (more) fetch();
+                load_frags(std::integral_constant<int, 0>{}, cur, std::integral_constant<int, 0>{});
+                body_steps(cur, no);
+                last_step(cur, no, no);
+                if (more) commit(cur ^ 1);
+                __syncthreads();
+            }
+        }
+
+        // ---- finish the segment
+        // Lane and wavefront ids as this iteration's own values: what the code below derives
+        // from them (hundreds of LDS and output offsets) is the same for every segment, and
+        // the compiler would otherwise compute all of it before the segment loop and keep it
+        // in registers through the K loop, at the price of spills inside that loop.
+        int elane = lane, ewave = wave;
+        if constexpr (STREAMK) asm volatile("" : "+v"(elane), "+v"(ewave));
+        const int ewm = ewave / WGN, ewn = ewave % WGN;
+        // column sums of the segment: elane l holds column l % 32 of each fragment for the
+        // k-values 8 (l / 32) .. + 7 of every k16 step, so the two halves of the wavefront
+        // add up to the column sum (valid in lanes 0..31)
+        float csv[COLSUM ? FN : 1];
+        if constexpr (COLSUM) {
+            static_for<FN>([&](auto j) { csv[j] = cs[j] + __shfl_xor(cs[j], 32, 64); });
+        }
+        if (!streamk && g.splits > 1) {
+            // equal K parts over gridDim.z: partial sums in accumulator order
+            // [(z*nb + tile)][ewave][frag][reg][elane] for the reduction kernel
+            if constexpr (COLSUM) {
+                if (cs_wave) {
+                    float* part = g.ws + (size_t)g.splits * nb * (BM * BN) + (size_t)blockIdx.z * g.N;
+                    static_for<FN>([&](auto j) {
+                        const int col = col0 + ewn * WTN + j * 32 + elane;
+                        if (elane < 32 && col < g.N) part[col] = csv[j];
+                    });
+                }
+            }
+            float* w = g.ws + ((size_t)blockIdx.z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
+                       (size_t)ewave * (FM * FN * 16 * 64) + elane;
+            static_for<FM * FN>([&](auto f) {
+                static_for<16>([&](auto r) { w[(f * 16 + r) * 64] = acc[f][r()]; });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+#ifdef TESS_STAMPS
+            wait_vmcnt<0>(); TESS_STAMP(4 + 4 * seg);
+#endif
+            break;
+        }
+        // ---- shared tiles (STREAMK).  The tile's P contributors -- the main workgroup
+        // (p = 0) and the tail workgroups that hold parts of its tail, in ascending K order --
+        // announce themselves on the tile's control word as they finish.  All but the last
+        // to arrive write their accumulators, as an fp32 tile in row order, to their partial
+        // slot and then raise the slot's flag.  The last one waits for those flags (their
+        // owners have arrived already and only have the write left: the wait is short and
+        // never depends on a workgroup that has not started), adds the partials to its own
+        // sum IN ASCENDING K ORDER, its own contribution at its place, and runs the epilogue.
+        // Words carry the call's token, so that whatever an earlier call or another user of
+        // the memory left there reads as "nobody yet"; the last arrival puts the words it
+        // used back to that state (a replayed graph passes the same token again).  Partials
+        // are written through and read past the per-XCD L2 (sc1), flags and control words
+        // are agent-scope atomics: no cache-wide write-back or invalidate is involved.
+        constexpr int SC1 = 16;
+        constexpr uint32_t SLOT_BYTES = BM * BN * 4 + 1024;
+        int P = 1, mine = 0, sk_jf = 0;
+        bool writer = false;
+        auto slot_index = [&](int p) {
+            // 64 slots per XCD: 0..31 the tails' (tile + tail workgroup, a chain without repeats), 32.. the mains'
+            return sk_xcd * 64 + (p == 0 ? 32 + sk_tl : sk_tl + sk_jf + p - 1);
+        };
+        auto slot_rsrc = [&](int p) {
+            char* base = (char*)g.ws + (size_t)slot_index(p) * SLOT_BYTES;
+            return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)SLOT_BYTES, 0x00020000);
+        };
+        if constexpr (STREAMK) {
+            sk_jf = (sk_tl * sk_L) / sk_upw;
+            const int jl = ((sk_tl + 1) * sk_L - 1) / sk_upw;
+            P = 2 + jl - sk_jf;
+            mine = kt_begin == 0 ? 0 : 1 + (sk_i - sk_nx) - sk_jf;
+            volatile int* sh = (volatile int*)lds;
+            if (tid == 0) {
+                unsigned long long* ctrl = g.sk_ctrl + (sk_first + sk_tl);
+                unsigned long long old = __hip_atomic_load(ctrl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                unsigned long long des;
+                do {
+                    des = ((old >> 16) == g.sk_token ? old : (g.sk_token << 16)) + 1;
+                } while (!__hip_atomic_compare_exchange_strong(ctrl, &old, des, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT));
+                const int arrival = (int)(des & 0xffffu);          // 1 .. P
+                int bad = 0;
+                if (arrival == P) {
+                    for (int p = 0; p < P; ++p) {
+                        if (p == mine) continue;
+                        unsigned long long* f = g.sk_flags + slot_index(p);
+                        int spins = 0;
+                        while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != g.sk_token) {
+                            if (++spins > (1 << 22)) { bad = 1; break; }      // bounded: never hang the device
+                            __builtin_amdgcn_s_sleep(8);
+                        }
+                        __hip_atomic_store(f, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    __hip_atomic_store(ctrl, g.sk_token << 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                sh[0] = arrival;
+                sh[1] = bad;
+            }
+            lds_barrier();
+            writer = __builtin_amdgcn_readfirstlane(sh[0]) < P;
+            if (__builtin_amdgcn_readfirstlane(sh[1])) {
+                // a contributor never delivered (cannot happen on a healthy device): poison
+                // the tile rather than pass off a partial sum as the result
+                static_for<FM * FN>([&](auto x) { static_for<16>([&](auto r) { acc[x][r()] = __builtin_nanf(""); }); });
+            }
+            lds_barrier();                             // the words are overwritten below
+            // partial column sums travel in the last KiB of the slot
+            if constexpr (COLSUM) {
+                if (cs_wave && elane < 32) {
+                    const uint32_t tail_off = (uint32_t)(BM * BN * 4 + (ewn * WTN + elane) * 4);
+                    if (writer) {
+                        const auto rs = slot_rsrc(mine);
+                        static_for<FN>([&](auto j) {
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(csv[j]), rs, tail_off + j * 128, 0, SC1);
+                        });
+                    } else {
+                        static_for<FN>([&](auto j) {
+                            float run = 0.0f;
+                            for (int p = 0; p < P; ++p) {
+                                float v = csv[j];
+                                if (p != mine)
+                                    v = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(slot_rsrc(p), tail_off + j * 128, 0, SC1));
+                                run = p == 0 ? v : run + v;
+                            }
+                            csv[j] = run;
+                        });
+                    }
+                }
+            }
+        }
+        TESS_STAMP(3 + 4 * seg);
+        if constexpr (COLSUM) {
+            if (cs_wave && !writer) {
+                static_for<FN>([&](auto j) {
+                    const int col = col0 + ewn * WTN + j * 32 + elane;
+                    if (elane < 32 && col < g.N) g.colsum[col] = g.accumulate ? g.colsum[col] + csv[j] : csv[j];
+                });
+            }
+        }
+        // ---- epilogue.  The wavefront passes its accumulators through a private slice of
+        // the (now idle) LDS, half of its tile at a time, to turn the MFMA fragment layout
+        // into rows: a short rolled loop then handles four adjacent columns per lane, so
+        // every output row leaves as one contiguous run and the code stays small.
+        {
+            constexpr int HR = WTM / 2;                    // rows per half
+            constexpr int ROWB = WTN * 4;                  // fp32 bytes per row of the wave tile
+            constexpr int CPR = WTN / 4;                   // 16-byte chunks per row
+            constexpr int RPI = 64 / CPR;                  // rows per 64-lane pass
+            static_assert(FM % 2 == 0, "two halves of whole fragments");
+            static_assert(NSTAGE * STAGE_BYTES >= WGM * WGN * HR * ROWB, "LDS holds half a tile in fp32");
+            char* slice = lds + ewave * (HR * ROWB);
+            const int esize = g.out_f32 ? 4 : 2;
+            const bool vec = ((g.ldo * esize) % 16 == 0) &&
+                             ((reinterpret_cast<uintptr_t>(g.out) & 15u) == 0) &&
+                             (!g.preact || (reinterpret_cast<uintptr_t>(g.preact) & 15u) == 0) &&
+                             (!g.zin || (((reinterpret_cast<uintptr_t>(g.zin) & 7u) == 0) && (g.ldz % 4 == 0)));
+            // chunk c of row r is kept at chunk c ^ (8 * bit 2 of r): the two half-waves of
+            // a fragment (rows r and r+4) then write to different banks
+            constexpr int NIT = HR / RPI;                  // passes of the drain loop per half
+            // dX through GELU': the pre-activations are fetched before the accumulators are staged,
+            // so that their latency is hidden behind the LDS traffic instead of sitting in the loop
+            const bool dgelu = !writer && g.zin && g.dact == TESS_ACT_GELU_ERF && !g.out_f32 && !g.in_f32 &&
+                               !g.preact && g.act == TESS_ACT_NONE;
+            static_for<2>([&](auto half) {
+                const int wrow0 = row0 + ewm * WTM + half * HR, wcol0 = col0 + ewn * WTN;
+                // a lane serves the same four columns in every pass
+                const int c = elane % CPR, col = wcol0 + c * 4;
+                // byte offset, inside a partial slot, of this lane's four columns in pass 0
+                const uint32_t poff = (uint32_t)(((ewm * WTM + half * HR + elane / CPR) * BN + ewn * WTN + c * 4) * 4);
+                u32x2 zr[NIT];
+                if (dgelu) {
+                    static_for<NIT>([&](auto it) {
+                        const int row = wrow0 + it * RPI + elane / CPR;
+                        zr[it] = u32x2{0u, 0u};
+                        if (row < g.M && col < g.N) {
+                            const uint16_t* zp = (const uint16_t*)g.zin + (int64_t)row * g.ldz + col;
+                            if (vec && col + 3 < g.N) {
+                                zr[it] = *(const u32x2*)zp;
+                            } else {
+                                for (int e = 0; e < 4; ++e)
+                                    if (col + e < g.N) zr[it][e >> 1] |= (uint32_t)zp[e] << (16 * (e & 1));
+                            }
+                        }
+                    });
+                }
+                // the other contributor's half tile of a tile shared by two (the usual case) is
+                // fetched before the accumulators are staged, like the pre-activations above
+                floatx4 pv[STREAMK ? NIT : 1];
+                const bool fold2 = STREAMK && !writer && P == 2;
+                if constexpr (STREAMK) {
+                    if (fold2) {
+                        const auto rs = slot_rsrc(1 - mine);
+                        static_for<NIT>([&](auto it) {
+                            pv[it] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs, poff, it * (RPI * BN * 4), SC1));
+                        });
+                    }
+                }
+                static_for<FM / 2>([&](auto ii) {
+                    static_for<FN>([&](auto j) {
+                        constexpr int f = (half * (FM / 2) + ii) * FN + j;
+                        const int cl = j * 32 + (elane & 31);
+                        static_for<16>([&](auto r) {
+                            const int rl = ii * 32 + 8 * (r / 4) + 4 * (elane >> 5) + (r % 4);
+                            const int phys = (cl >> 2) ^ (((rl >> 2) & 1) << 3);
+                            *(float*)(slice + rl * ROWB + phys * 16 + (cl & 3) * 4) = acc[f][r()];
+                        });
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                });
+                if constexpr (STREAMK) {
+                    if (writer) {
+                        // this contribution as it stands (no bias, no activation), to its slot
+                        const auto rs = slot_rsrc(mine);
+    #pragma unroll 4
+                        for (int it = 0; it < NIT; ++it) {
+                            const int rl = it * RPI + elane / CPR;
+                            const int phys = c ^ (((rl >> 2) & 1) << 3);
+                            const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
+                            if (wrow0 + rl < g.M && col < g.N)
+                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs, poff, it * (RPI * BN * 4), SC1);
+                        }
+                        return;
+                    }
+                    if (fold2) {
+                        // two contributions: the sum does not depend on the order
+                        static_for<NIT>([&](auto it) {
+                            const int rl = it * RPI + elane / CPR;
+                            const int phys = c ^ (((rl >> 2) & 1) << 3);
+                            floatx4* q = (floatx4*)(slice + rl * ROWB + phys * 16);
+                            if (wrow0 + rl < g.M && col < g.N) *q = *q + pv[it];
+                        });
+                    } else if (P > 2) {
+                        // three or more: ascending K order, this workgroup's own sum at its place
+                        for (int it = 0; it < NIT; ++it) {
+                            const int rl = it * RPI + elane / CPR;
+                            const int phys = c ^ (((rl >> 2) & 1) << 3);
+                            floatx4* q = (floatx4*)(slice + rl * ROWB + phys * 16);
+                            if (wrow0 + rl < g.M && col < g.N) {
+                                floatx4 run = {0.f, 0.f, 0.f, 0.f};
+                                for (int p = 0; p < P; ++p) {
+                                    floatx4 v = *q;
+                                    if (p != mine)
+                                        v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                                            slot_rsrc(p), poff, it * (RPI * BN * 4), SC1));
+                                    run = p == 0 ? v : run + v;
+                                }
+                                *q = run;
+                            }
                         }
                     }
-                });
-            }
-            static_for<FM / 2>([&](auto ii) {
-                static_for<FN>([&](auto j) {
-                    constexpr int f = (half * (FM / 2) + ii) * FN + j;
-                    const int cl = j * 32 + (lane & 31);
-                    static_for<16>([&](auto r) {
-                        const int rl = ii * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                        const int phys = (cl >> 2) ^ (((rl >> 2) & 1) << 3);
-                        *(float*)(slice + rl * ROWB + phys * 16 + (cl & 3) * 4) = acc[f][r()];
-                    });
-                    __builtin_amdgcn_sched_barrier(0);
-                });
-            });
-            // fetch the bias of the lane's four columns once
-            floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
-            if (g.bias) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (col + e < g.N) bias4[e] = bf16_bits_to_f32(((const uint16_t*)g.bias)[col + e]);
-            }
-            auto drain = [&](auto mode) {
-#pragma unroll 4
-                for (int it = 0; it < NIT; ++it) {
-                    const int rl = it * RPI + lane / CPR;
-                    const int phys = c ^ (((rl >> 2) & 1) << 3);
-                    const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
-                    const int row = wrow0 + rl;
-                    if (row < g.M && col < g.N) emit4<mode>(g, row, col, v, bias4, vec);
                 }
-            };
-            if (dgelu) {
-                static_for<NIT>([&](auto it) {
-                    const int rl = it * RPI + lane / CPR;
-                    const int phys = c ^ (((rl >> 2) & 1) << 3);
-                    const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
-                    const int row = wrow0 + rl;
-                    if (row < g.M && col < g.N) emit4<MODE_BF16_DGELU>(g, row, col, v, bias4, vec, zr[it]);
-                });
+                // fetch the bias of the lane's four columns once
+                floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
+                if (g.bias) {
+    #pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < g.N) bias4[e] = bf16_bits_to_f32(((const uint16_t*)g.bias)[col + e]);
+                }
+                auto drain = [&](auto mode) {
+    #pragma unroll 4
+                    for (int it = 0; it < NIT; ++it) {
+                        const int rl = it * RPI + elane / CPR;
+                        const int phys = c ^ (((rl >> 2) & 1) << 3);
+                        const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
+                        const int row = wrow0 + rl;
+                        if (row < g.M && col < g.N) emit4<mode>(g, row, col, v, bias4, vec);
+                    }
+                };
+                if (dgelu) {
+                    static_for<NIT>([&](auto it) {
+                        const int rl = it * RPI + elane / CPR;
+                        const int phys = c ^ (((rl >> 2) & 1) << 3);
+                        const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
+                        const int row = wrow0 + rl;
+                        if (row < g.M && col < g.N) emit4<MODE_BF16_DGELU>(g, row, col, v, bias4, vec, zr[it]);
+                    });
+                }
+                else if (g.zin || g.preact || g.act == TESS_ACT_GELU_TANH || (g.out_f32 && g.act != TESS_ACT_NONE))
+                    drain(std::integral_constant<int, MODE_GENERIC>{});
+                else if (g.out_f32 && g.accumulate) drain(std::integral_constant<int, MODE_F32_ACC>{});
+                else if (g.out_f32) drain(std::integral_constant<int, MODE_F32>{});
+                else if (g.act == TESS_ACT_GELU_ERF) drain(std::integral_constant<int, MODE_BF16_GELU>{});
+                else drain(std::integral_constant<int, MODE_BF16>{});
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            if constexpr (STREAMK) {
+                if (writer) {
+                    wait_vmcnt<0>();                   // every store of this wavefront is acknowledged
+                    lds_barrier();                     // ... and of the others
+                    if (tid == 0)
+                        __hip_atomic_store(g.sk_flags + slot_index(mine), g.sk_token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
-            else if (g.zin || g.preact || g.act == TESS_ACT_GELU_TANH || (g.out_f32 && g.act != TESS_ACT_NONE))
-                drain(std::integral_constant<int, MODE_GENERIC>{});
-            else if (g.out_f32 && g.accumulate) drain(std::integral_constant<int, MODE_F32_ACC>{});
-            else if (g.out_f32) drain(std::integral_constant<int, MODE_F32>{});
-            else if (g.act == TESS_ACT_GELU_ERF) drain(std::integral_constant<int, MODE_BF16_GELU>{});
-            else drain(std::integral_constant<int, MODE_BF16>{});
-            __builtin_amdgcn_sched_barrier(0);
+        }
 #ifdef TESS_STAMPS
-            if constexpr (half == 0) { TESS_STAMP(4); }
-            else { TESS_STAMP(5); wait_vmcnt<0>(); TESS_STAMP(6); }
+        wait_vmcnt<0>(); TESS_STAMP(4 + 4 * seg);
 #endif
-        });
+        if (!streamk) break;
+        lds_barrier();                                 // the next segment's loads overwrite the LDS
     }
 }
 
@@ -956,12 +1193,12 @@ __global__ __launch_bounds__(256) void tess_splitk_reduce_kernel(GemmArgs g)
 }
 
 template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT,
-          bool COLSUM = false>
+          bool COLSUM = false, bool STREAMK = false>
 static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
-    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT, COLSUM>;
+    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT, COLSUM, STREAMK>;
     // the dynamic LDS limit is a per-device attribute of the kernel: set it once per device
     // (a bit per device id; setting it twice from two threads is harmless)
     static std::atomic<uint64_t> attr_done{0};
@@ -976,8 +1213,13 @@ static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
     }
     const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     GemmArgs a = g;
-    a.splits = p.splits;
-    hipLaunchKernelGGL(kern, dim3(tiles, 1, p.splits), dim3(NT), lds_bytes, s, a);
+    a.splits = p.splits > 1 ? p.splits : 1;
+    if constexpr (STREAMK) {
+        // one workgroup per worker, the fix-up happens inside the kernel
+        hipLaunchKernelGGL(kern, dim3(p.sk_workers, 1, 1), dim3(NT), lds_bytes, s, a);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(kern, dim3(tiles, 1, a.splits), dim3(NT), lds_bytes, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.splits > 1) {
@@ -989,14 +1231,14 @@ static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
     return e;
 }
 
-template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool DIRECT>
+template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool DIRECT, bool STREAMK = false>
 static hipError_t launch_layout(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
-    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, false, DIRECT>(g, p, s);
-    if (g.a_kc && g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, true, DIRECT>(g, p, s);
+    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, false, DIRECT, false, STREAMK>(g, p, s);
+    if (g.a_kc && g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, true, DIRECT, false, STREAMK>(g, p, s);
     if (!g.a_kc && !g.b_kc) {
-        if (g.colsum) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT, true>(g, p, s);
-        return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT>(g, p, s);
+        if (g.colsum) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT, true, STREAMK>(g, p, s);
+        return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT, false, STREAMK>(g, p, s);
     }
     return hipErrorInvalidValue;
 }
@@ -1050,8 +1292,10 @@ hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     if (p.bm == 256 && p.bn == 256) {
         if (!p.direct) return hipErrorInvalidValue;
+        if (p.sk_workers > 0) return launch_layout<256, 256, 64, 2, 2, 2, true, true>(g, p, s);
         return launch_layout<256, 256, 64, 2, 2, 2, true>(g, p, s);
     }
+    if (p.sk_workers > 0) return hipErrorInvalidValue;     // stream-K exists for 256 x 256 tiles only
     if (p.bm == 128 && p.bn == 128) {
         if (!p.direct) return launch_layout<128, 128, 64, 2, 2, 2, false>(g, p, s);
         return launch_layout<128, 128, 64, 3, 2, 2, true>(g, p, s);
