@@ -123,6 +123,25 @@ tess_status tess_linear_bwd_dw(const tess_desc* desc,
                                void* dw_out, int64_t lddw, int accumulate,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* tess_linear_bwd_dw for callers that cannot allocate or hand over device memory at the
+ * call: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments and results as tess_linear_bwd_dw without the workspace: the
+ * K-split partial sums go to a scratch array that is part of the library's code object
+ * (tess_noalloc_scratch_bytes() = 80 MiB per device, held until the process ends).  The
+ * call allocates nothing; its first use on a device looks the array's address up.
+ *   - A launch plan that needs more scratch than that returns TESS_ERR_WORKSPACE (check
+ *     with tess_linear_workspace_bytes(desc, TESS_OP_BWD_DW)); nothing is enqueued then.
+ *   - Every call on a device shares that device's array: calls that may overlap on one
+ *     device (different streams, different threads) race on it and must be ordered by
+ *     the caller.  Nothing in it has to start at zero (every partial tile is written
+ *     before it is read), so the last call's contents do no harm.                     */
+tess_status tess_linear_bwd_dw_noalloc(const tess_desc* desc,
+                                       const void* const* x_panels, int64_t ldx,
+                                       const void* const* dy_panels, int64_t lddy,
+                                       void* dw_out, int64_t lddw, int accumulate,
+                                       void* hip_stream);
+size_t tess_noalloc_scratch_bytes(void);
+
 /* Input gradient through the activation that produced this layer's input (the MLP's
  * middle activation, Section 2.4): the same sum as tess_linear_bwd_dx, multiplied
  * element by element by the derivative of `act` at the saved pre-activation,

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
 
 EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
            "tess_linear_bwd_dx_act", "tess_linear_bwd_dw_bias",
+           "tess_linear_bwd_dw_noalloc", "tess_noalloc_scratch_bytes",
            "tess_linear_bwd_dx_step", "tess_linear_bwd_dw_step",
            "tess_layernorm_row_sums", "tess_layernorm_normalize",
            "tess_layernorm_bwd_row_sums", "tess_layernorm_bwd_apply",
@@ -62,6 +63,10 @@ def lib():
         L.tess_linear_bwd_dx.argtypes = [dp, pp, i64, pp, i64, vp, i64, vp, sz, vp]
         L.tess_linear_bwd_dw.restype = cint
         L.tess_linear_bwd_dw.argtypes = [dp, pp, i64, pp, i64, vp, i64, cint, vp, sz, vp]
+        L.tess_linear_bwd_dw_noalloc.restype = cint
+        L.tess_linear_bwd_dw_noalloc.argtypes = [dp, pp, i64, pp, i64, vp, i64, cint, vp]
+        L.tess_noalloc_scratch_bytes.restype = sz
+        L.tess_noalloc_scratch_bytes.argtypes = []
         L.tess_linear_bwd_dx_act.restype = cint
         L.tess_linear_bwd_dx_act.argtypes = [dp, pp, i64, pp, i64, vp, i64, cint, vp, i64, vp, sz, vp]
         L.tess_linear_bwd_dw_bias.restype = cint
@@ -424,3 +429,21 @@ def linear_bwd_dw(desc, x_panels, dy_panels, dw_out, accumulate=False, workspace
                                   1 if accumulate else 0, wsp, wsb, _stream(stream))
     if st:
         raise TessError(st, "tess_linear_bwd_dw")
+
+
+def linear_bwd_dw_noalloc(desc, x_panels, dy_panels, dw_out, accumulate=False, stream=None):
+    """tess_linear_bwd_dw_noalloc: linear_bwd_dw with the library's own static scratch."""
+    m, kb, n = block_shape(desc)
+    _dtypes(x_panels=(desc.in_dtype, x_panels), dy_panels=(desc.in_dtype, dy_panels),
+            dw_out=(F32 if accumulate else desc.out_dtype, dw_out))
+    xp, ldx = _panel_array(x_panels, m, kb, "x_panels", desc.in_dtype)
+    dyp, lddy = _panel_array(dy_panels, m, n, "dy_panels", desc.in_dtype)
+    op, ldo = _out(dw_out, kb, n, "dw_out", F32 if accumulate else desc.out_dtype)
+    st = lib().tess_linear_bwd_dw_noalloc(ctypes.byref(desc), xp, ldx, dyp, lddy, op, ldo,
+                                          1 if accumulate else 0, _stream(stream))
+    if st:
+        raise TessError(st, "tess_linear_bwd_dw_noalloc")
+
+
+def noalloc_scratch_bytes():
+    return lib().tess_noalloc_scratch_bytes()

@@ -5,6 +5,7 @@
 #include "tesseract_diag.h"
 
 #include <atomic>
+#include <mutex>
 #include <random>
 
 namespace tess {
@@ -198,6 +199,37 @@ static tess_status run(GemmArgs& g, void* workspace, size_t workspace_bytes, voi
 
 }  // namespace tess
 
+// Scratch of tess_linear_bwd_dw_noalloc: part of the code object, one copy per device, held
+// until the process ends.  In host code the array's name is only a handle: the device
+// address comes from hipGetSymbolAddress, once per device with that device current.
+#define TESS_NOALLOC_SCRATCH_BYTES (80u << 20)
+static __device__ __align__(256) unsigned char scratch[TESS_NOALLOC_SCRATCH_BYTES];
+
+namespace tess {
+
+static hipError_t scratch_of_current_device(void** out)
+{
+    constexpr int kMaxDev = 64;
+    static void* ptrs[kMaxDev] = {};
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return hipSuccess;
+}
+
+}  // namespace tess
+
 using namespace tess;
 
 extern "C" {
@@ -330,7 +362,8 @@ tess_status tess_linear_bwd_dx_act(const tess_desc* desc, const void* const* dy_
 static tess_status bwd_dw_impl(const tess_desc* desc, const void* const* x_panels, int64_t ldx,
                                const void* const* dy_panels, int64_t lddy, void* dw_out,
                                int64_t lddw, void* dbias_out, bool with_bias, int accumulate,
-                               void* workspace, size_t workspace_bytes, void* hip_stream)
+                               void* workspace, size_t workspace_bytes, void* hip_stream,
+                               bool static_scratch = false)
 {
     tess_status st = check_desc(desc);
     if (st != TESS_OK) return st;
@@ -349,6 +382,17 @@ static tess_status bwd_dw_impl(const tess_desc* desc, const void* const* x_panel
     g.accumulate = accumulate;
     g.a_kc = 0; g.b_kc = 0; g.in_f32 = desc->in_dtype == TESS_F32;
     g.colsum = with_bias ? static_cast<float*>(dbias_out) : nullptr;
+    if (static_scratch) {
+        // the size check needs no device: it comes before the first HIP call
+        Plan p;
+        const tess_status ps = make_plan(g, p);
+        if (ps != TESS_OK) return ps;
+        if (p.ws_bytes > TESS_NOALLOC_SCRATCH_BYTES) return TESS_ERR_WORKSPACE;
+        if (p.ws_bytes > 0) {
+            if (scratch_of_current_device(&workspace) != hipSuccess) return TESS_ERR_HIP;
+            workspace_bytes = TESS_NOALLOC_SCRATCH_BYTES;
+        }
+    }
     return run(g, workspace, workspace_bytes, hip_stream);
 }
 
@@ -360,6 +404,16 @@ tess_status tess_linear_bwd_dw(const tess_desc* desc, const void* const* x_panel
     return bwd_dw_impl(desc, x_panels, ldx, dy_panels, lddy, dw_out, lddw, nullptr, false,
                        accumulate, workspace, workspace_bytes, hip_stream);
 }
+
+tess_status tess_linear_bwd_dw_noalloc(const tess_desc* desc, const void* const* x_panels, int64_t ldx,
+                                       const void* const* dy_panels, int64_t lddy, void* dw_out,
+                                       int64_t lddw, int accumulate, void* hip_stream)
+{
+    return bwd_dw_impl(desc, x_panels, ldx, dy_panels, lddy, dw_out, lddw, nullptr, false,
+                       accumulate, nullptr, 0, hip_stream, true);
+}
+
+size_t tess_noalloc_scratch_bytes(void) { return TESS_NOALLOC_SCRATCH_BYTES; }
 
 tess_status tess_linear_bwd_dw_bias(const tess_desc* desc, const void* const* x_panels,
                                     int64_t ldx, const void* const* dy_panels, int64_t lddy,
