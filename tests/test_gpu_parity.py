@@ -58,6 +58,35 @@ def test_small_integers_are_bit_exact(q, d, m, kb, n, dtype):
         assert np.array_equal(f64(got[key]), want[key]), key
 
 
+# Launch shapes that the cost model does not pick for any shape above, forced with the
+# diagnostic override: (tile, K splits, (q, d, m, kb, n)).  tests/test_plan_coverage.py checks
+# on the host that, with these, every kernel variant x split / no split x call is exercised.
+FORCED = [
+    (128, 3, (3, 2, 200, 72, 136)),        # register-staged loader (ragged K) with K splits
+    (128, 1, (2, 2, 264, 64, 520)),
+    (256, 2, (2, 2, 1024, 1024, 1024)),    # 256 x 256 tiles, K split, several tiles
+    (256, 1, (2, 2, 1024, 1024, 1024)),
+    (256, 3, (2, 1, 576, 320, 832)),       # ragged M and N edges on 256 x 256 tiles, uneven split
+]
+
+
+@pytest.mark.parametrize("tile,splits,shape", FORCED)
+def test_forced_launch_shapes_are_bit_exact(tile, splits, shape):
+    q, d, m, kb, n = shape
+    inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=17, integers=True)
+    try:
+        B.set_plan_override(tile=tile, k_splits=splits, stream_k=0)
+        desc = B.make_desc(q, d, 0, 0, 0, m * q * d, kb * q, n * q, B.BF16, B.F32)
+        for op in (B.OP_FWD, B.OP_BWD_DX, B.OP_BWD_DW):
+            assert tess.plan(desc, op) == (tile, tile, splits)
+        got = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "f32", act="none")
+    finally:
+        B.set_plan_override(0, 0, -1)
+    want = oracle_share(inp["x"], inp["w"], inp["bias"], inp["dy"], act="none")
+    for key in ("y", "dx", "dw"):
+        assert np.array_equal(f64(got[key]), want[key]), key
+
+
 @pytest.mark.parametrize("act", ["none", "gelu_erf", "gelu_tanh"])
 @pytest.mark.parametrize("dtype,shape", [("bf16", (2, 2, 256, 128, 384)), ("f32", (2, 2, 96, 80, 72))])
 def test_epilogue_forms(act, dtype, shape):
