@@ -85,7 +85,12 @@ typedef struct {
  *   bias        : device, [n] in in_dtype (slice j of the bias), or NULL
  *   c_out       : device, [m, n], ldc, out_dtype
  *   preact_out  : device, [m, n], ldc, out_dtype, or NULL: receives the sum plus
- *                 bias before the activation (what a GELU backward needs)
+ *                 bias before the activation (what a GELU backward needs); asking for it
+ *                 does not change c_out
+ *   TESS_ACT_GELU_ERF is evaluated in fp32 with the library erf when c_out is fp32 and,
+ *   when c_out is bf16, with a branch-free erfc form whose absolute error (< 5e-7) is far
+ *   below a bf16 step: the two are different roundings of the same function, and a bf16
+ *   result is not always the rounding of the fp32 result.
  *   workspace   : device scratch of >= tess_linear_workspace_bytes(desc, TESS_OP_FWD)
  *                 bytes, 256-byte aligned; may be NULL when that size is 0.        */
 tess_status tess_linear_fwd(const tess_desc* desc,

@@ -348,7 +348,8 @@ void orc_layernorm_from_sums(const double* x, int64_t m, int64_t w, int64_t ldx,
 {
     for (int64_t r = 0; r < m; ++r) {
         const double mean = sums[2 * r] / (double)n_total;
-        const double var = sums[2 * r + 1] / (double)n_total - mean * mean;
+        /* a variance is non-negative; the difference of the two moments may round below zero */
+        const double var = fmax(sums[2 * r + 1] / (double)n_total - mean * mean, 0.0);
         const double rstd = 1.0 / sqrt(var + eps);
         for (int64_t u = 0; u < w; ++u) xhat_out[r * w + u] = (x[r * ldx + u] - mean) * rstd;
     }
@@ -380,7 +381,7 @@ void orc_layernorm_bwd_from_sums(const double* xhat, const double* g, int64_t m,
 {
     for (int64_t r = 0; r < m; ++r) {
         const double mean = sums_fwd[2 * r] / (double)n_total;
-        const double var = sums_fwd[2 * r + 1] / (double)n_total - mean * mean;
+        const double var = fmax(sums_fwd[2 * r + 1] / (double)n_total - mean * mean, 0.0);
         const double rstd = 1.0 / sqrt(var + eps);
         for (int64_t u = 0; u < w; ++u) {
             const double xh = xhat[r * ldx + u];

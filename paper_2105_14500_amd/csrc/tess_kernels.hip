@@ -132,7 +132,7 @@ __device__ __forceinline__ void store_out(const GemmArgs& g, int row, int col, f
         if (g.out_f32) ((float*)g.preact)[o] = z;
         else ((uint16_t*)g.preact)[o] = f32_to_bf16_bits(z);
     }
-    float y = apply_act(z, g.act);
+    float y = (!g.out_f32 && g.act == TESS_ACT_GELU_ERF) ? gelu_erf_fast(z) : apply_act(z, g.act);
     if (g.zin) y *= apply_act_grad(load_in(g.zin, (int64_t)row * g.ldz + col, g.in_f32), g.dact);
     if (g.out_f32) {
         float* op = (float*)g.out + o;
@@ -448,7 +448,7 @@ __device__ __forceinline__ u32x2 pack_bf16x4(floatx4 v)
 }
 
 enum : int { MODE_BF16 = 0, MODE_BF16_GELU = 1, MODE_F32 = 2, MODE_F32_ACC = 3, MODE_GENERIC = 4,
-             MODE_BF16_DGELU = 5 };
+             MODE_BF16_DGELU = 5, MODE_BF16_GELU_PRE = 6 };
 
 template <int MODE>
 __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, floatx4 v, floatx4 bias,
@@ -456,8 +456,12 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
 {
     const bool out_f32 = MODE == MODE_GENERIC ? (g.out_f32 != 0) : (MODE == MODE_F32 || MODE == MODE_F32_ACC);
     const bool accumulate = MODE == MODE_GENERIC ? (g.accumulate != 0) : (MODE == MODE_F32_ACC);
-    const bool preact = MODE == MODE_GENERIC ? (g.preact != nullptr) : false;
-    const int act = MODE == MODE_GENERIC ? g.act : (MODE == MODE_BF16_GELU ? TESS_ACT_GELU_ERF : TESS_ACT_NONE);
+    // MODE_BF16_GELU_PRE: the MLP up-projection that keeps its pre-activation for the backward
+    // pass; same GELU evaluation as MODE_BF16_GELU, so the layer's output does not depend on
+    // whether the pre-activation is asked for
+    const bool preact = MODE == MODE_GENERIC ? (g.preact != nullptr) : (MODE == MODE_BF16_GELU_PRE);
+    const int act = MODE == MODE_GENERIC ? g.act
+                    : ((MODE == MODE_BF16_GELU || MODE == MODE_BF16_GELU_PRE) ? TESS_ACT_GELU_ERF : TESS_ACT_NONE);
     const int nvalid = g.N - col < 4 ? g.N - col : 4;
     v += bias;
     const int64_t o = (int64_t)row * g.ldo + col;
@@ -485,7 +489,10 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
             v[e] *= apply_act_grad(load_in(g.zin, (int64_t)row * g.ldz + col + e, g.in_f32), g.dact);
     }
     if (act != TESS_ACT_NONE) {
-        if (MODE == MODE_BF16_GELU) {
+        // every 2-byte erf-GELU output takes the same evaluation, whichever kernel or drain
+        // produces it; fp32 outputs take the library erf
+        if (MODE == MODE_BF16_GELU || MODE == MODE_BF16_GELU_PRE ||
+            (MODE == MODE_GENERIC && !out_f32 && act == TESS_ACT_GELU_ERF)) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = gelu_erf_fast(v[e]);
         } else {
@@ -1110,6 +1117,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
                         if (row < g.M && col < g.N) emit4<MODE_BF16_DGELU>(g, row, col, v, bias4, vec, zr[it]);
                     });
                 }
+                else if (g.preact && !g.zin && !g.out_f32 && g.act == TESS_ACT_GELU_ERF)
+                    drain(std::integral_constant<int, MODE_BF16_GELU_PRE>{});
                 else if (g.zin || g.preact || g.act == TESS_ACT_GELU_TANH || (g.out_f32 && g.act != TESS_ACT_NONE))
                     drain(std::integral_constant<int, MODE_GENERIC>{});
                 else if (g.out_f32 && g.accumulate) drain(std::integral_constant<int, MODE_F32_ACC>{});

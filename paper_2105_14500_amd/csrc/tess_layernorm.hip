@@ -77,7 +77,9 @@ __global__ __launch_bounds__(256) void tess_normalize_kernel(const void* x, int6
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= m) return;
     const float mean = sums[2 * row] * inv_n;
-    const float var = fmaf(-mean, mean, sums[2 * row + 1] * inv_n);
+    // E[X^2] - E[X]^2 is a variance: rounding can push the difference below zero for rows
+    // whose mean is large against their spread
+    const float var = fmaxf(fmaf(-mean, mean, sums[2 * row + 1] * inv_n), 0.0f);
     const float rstd = 1.0f / sqrtf(var + eps);
     constexpr int EPC = F32 ? 4 : 8;
     const char* src = (const char*)x + row * ldx * (F32 ? 4 : 2);
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(256) void tess_layernorm_bwd_kernel(const void* xha
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= m) return;
     const float mean = sums_fwd[2 * row] * inv_n;
-    const float var = fmaf(-mean, mean, sums_fwd[2 * row + 1] * inv_n);
+    const float var = fmaxf(fmaf(-mean, mean, sums_fwd[2 * row + 1] * inv_n), 0.0f);
     const float rstd = 1.0f / sqrtf(var + eps);
     const float A = sums_bwd[2 * row] * inv_n, Bc = sums_bwd[2 * row + 1] * inv_n;
     constexpr int EPC = F32 ? 4 : 8, ES = F32 ? 4 : 2;

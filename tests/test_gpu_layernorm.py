@@ -37,6 +37,26 @@ def test_row_sums_and_normalize(dtype, q, m, w):
     assert not torch.isnan(out).any()
 
 
+def test_constant_rows_with_a_large_mean_stay_finite():
+    """Rows whose mean dwarfs their spread: in fp32 the difference of the two moments can
+    round below zero by more than eps, and an unclamped variance would then give NaN.  A
+    constant row has variance 0: its normalised values are exactly 0."""
+    m, w = 16, 512
+    X = torch.full((m, w), 1000.0, dtype=torch.float32)
+    X[8:] += torch.arange(w, dtype=torch.float32)[None, :] * 1e-3        # tiny spread on half the rows
+    Xd = dev(X)
+    sums = torch.empty((m, 2), device="cuda:0")
+    B.layernorm_row_sums(Xd, sums)
+    for eps in (1e-5, 1e-12):
+        out = torch.full((m, w), float("nan"), device="cuda:0")
+        B.layernorm_normalize(Xd, sums, w, eps, out)
+        torch.cuda.synchronize()
+        assert torch.isfinite(out).all()
+        assert torch.all(out[:8] == 0.0)
+    want = orc.layernorm_from_sums(f64(X[:8]), orc.row_sums(f64(X[:8])), w, 1e-5)
+    assert np.all(want == 0.0)
+
+
 def test_row_sums_of_integers_are_exact_and_errors_are_reported():
     m, w = 64, 520
     r = np.random.default_rng(3)

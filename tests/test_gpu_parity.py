@@ -119,6 +119,25 @@ def test_bf16_output_is_rne_of_fp32_result():
         assert np.array_equal(f64(g16[key]), want), key
 
 
+@pytest.mark.parametrize("tile,splits", [(0, 0), (256, 1), (256, 2), (128, 3)])
+def test_bf16_gelu_output_does_not_depend_on_asking_for_the_preactivation(tile, splits):
+    """The MLP chain keeps the up-projection's pre-activation; a plain call does not.  Both must
+    produce the same H, bit for bit, in every launch shape (own drain, K-split reduction)."""
+    q, d, m, kb, n = 2, 2, 512, 256, 768
+    inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=21, w_std=0.1, bias_std=0.5)
+    try:
+        B.set_plan_override(tile=tile, k_splits=splits, stream_k=0)
+        a = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "bf16", act="gelu_erf")
+        b = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "bf16", act="gelu_erf",
+                      want_preact=True)
+    finally:
+        B.set_plan_override(0, 0, -1)
+    assert torch.equal(a["y"], b["y"])
+    z = orc.fwd_panels([f64(inp["x"][t]) for t in range(q)], [f64(inp["w"][t]) for t in range(q)],
+                       bias=f64(inp["bias"]), act=orc.ACT_NONE)
+    assert rel_err(b["preact"], z) <= TOL["bf16"]
+
+
 def test_gelu_of_exact_preactivations_bf16_out():
     """The 2-byte-output GELU epilogue on pre-activations that carry no rounding: inputs are
     multiples of 1/8 and weights are -1, 0, 1, so every sum is exact in fp32 and the only

@@ -582,6 +582,19 @@ def test_row_sums_and_layernorm_against_numpy():
     assert np.allclose(got, np.array([[-2.0, -1.0, 0.0, 3.0]]) / np.sqrt(3.5), atol=1e-15)
 
 
+def test_layernorm_variance_is_never_negative():
+    """Var[X] = E[X^2] - E[X]^2 (Section 3.2, "Other procedure") is a variance: where the
+    difference of the two moments rounds below zero it is taken as zero.  Sums whose
+    difference is slightly negative must give the result of a zero variance, not the NaN
+    of a negative one (eps smaller than the deficit)."""
+    x = np.array([[3.0, 3.0, 3.0, 3.0 + 1e-3]])
+    sums = np.array([[12.0 + 1e-3, 36.0 - 1e-3]])       # sum of squares too small by more than eps * n
+    out = orc.layernorm_from_sums(x, sums, 4, 1e-9)
+    assert np.isfinite(out).all()
+    mean = (12.0 + 1e-3) / 4
+    assert np.allclose(out, (x - mean) / np.sqrt(1e-9), rtol=1e-12)
+
+
 def test_layernorm_backward_against_central_differences():
     """X' of the paper's formula is the gradient of J = sum(c * xhat(X)) for fixed weights c
     (so dJ/dxhat = c): central differences of the oracle's own forward, element by element,
