@@ -16,7 +16,8 @@ OP_FWD, OP_BWD_DX, OP_BWD_DW, OP_BWD_DX_STEP, OP_BWD_DW_STEP = 0, 1, 2, 3, 4
 MAX_Q = 16
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtesseract_hip.so")
+# TESS_LIB_PATH: another build of the same sources (the host-only sanitizer build of the tests)
+LIB_PATH = os.environ.get("TESS_LIB_PATH") or os.path.join(_HERE, "libtesseract_hip.so")
 
 EXPORTS = ["tess_linear_fwd", "tess_linear_bwd_dx", "tess_linear_bwd_dw",
            "tess_linear_bwd_dx_act", "tess_linear_bwd_dw_bias",

@@ -203,7 +203,13 @@ static tess_status run(GemmArgs& g, void* workspace, size_t workspace_bytes, voi
 // until the process ends.  In host code the array's name is only a handle: the device
 // address comes from hipGetSymbolAddress, once per device with that device current.
 #define TESS_NOALLOC_SCRATCH_BYTES (80u << 20)
+#ifdef __HIPCC__
 static __device__ __align__(256) unsigned char scratch[TESS_NOALLOC_SCRATCH_BYTES];
+#else
+// host-only build of this file for the sanitizer tests (plain C++, no device code, kernel
+// launchers stubbed): a host array stands in, nothing ever dereferences it
+alignas(256) static unsigned char scratch[TESS_NOALLOC_SCRATCH_BYTES];
+#endif
 
 namespace tess {
 
@@ -219,8 +225,12 @@ static hipError_t scratch_of_current_device(void** out)
     std::lock_guard<std::mutex> lock(mu);
     if (!ptrs[dev]) {
         void* p = nullptr;
+#ifdef __HIPCC__
         e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
         if (e != hipSuccess) return e;
+#else
+        p = scratch;
+#endif
         if (!p) return hipErrorInvalidSymbol;
         ptrs[dev] = p;
     }
