@@ -19,7 +19,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16 MFMA, "2.5 PFLOP/s")
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, the published figure (256 CU x 4096 flop/clk x 2.4 GHz = 2516.6)
+PEAK_FP32_VECTOR_TFLOPS = 157.3   # MI355X fp32 vector ALU (the plain fp32 kernel of configuration 1)
 DEFAULT_WORKLOAD = "cfg4_q4d4_bf16_attn_h8192"   # the largest per-processor block shapes
 
 
@@ -30,7 +31,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--all", action="store_true", help="also time every other bf16 workload")
+    ap.add_argument("--no-sustained", action="store_true", help="skip the 3-second sustained loop")
+    ap.add_argument("--no-others", action="store_true", help="skip the other configurations")
     ap.add_argument("--graph", action="store_true",
                     help="with --sweep: record one step (all calls of all layers) into a HIP graph "
                          "after the warm-up and time replays of it, which removes the per-launch host "
@@ -189,17 +191,20 @@ def time_workload(torch, tess, B, wl, w, steps, warmup, on_device=False, graph=F
     ci = 0
     for st in layers:
         for name in names:
-            ms = sum(m[ci].elapsed_time(m[ci + 1]) for m in marks) / steps
+            per_step = sorted(m[ci].elapsed_time(m[ci + 1]) for m in marks)
+            ms = sum(per_step) / steps
+            ms_median, ms_min = per_step[len(per_step) // 2], per_step[0]
             ci += 1
             M, N, K = {"fwd": (st.L.m, st.L.n, st.L.kb * w.q), "dx": (st.L.m, st.L.kb, st.L.n * w.q),
                        "dw": (st.L.kb, st.L.n, st.L.m * w.q)}[name]
             tm, tn, ks = tess.plan(st.desc, {"fwd": B.OP_FWD, "dx": B.OP_BWD_DX, "dw": B.OP_BWD_DW}[name])
             calls[f"{st.L.name}.{name}"] = {"MxNxK": f"{M}x{N}x{K}", "tile": f"{tm}x{tn}", "k_splits": ks,
-                                            "ms": round(ms, 4),
+                                            "ms": round(ms, 4), "ms_median": round(ms_median, 4),
+                                            "ms_min": round(ms_min, 4),
                                             "tflops": round(st.flops_call / ms / 1e9, 1),
                                             "frac_peak": round(st.flops_call / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
     return {"ms_per_step": ms_step, "tflops": flops_step / ms_step / 1e9, "calls": calls,
-            "flops_step": flops_step, "layers": layers}
+            "flops_step": flops_step, "layers": layers, "step": step}
 
 
 def cpu_baseline(torch, w, layer_state, budget_s=24.0):
@@ -243,6 +248,93 @@ def cpu_baseline(torch, w, layer_state, budget_s=24.0):
             "sample": f"{w.name}/{L.name}: fwd and dX on {rows} evenly spaced output rows "
                       f"(all columns), dW on {rows_dw} output rows x first {cols} columns; "
                       f"{fl / 1e9:.1f} GFLOP in {dt:.1f} s, fp64"}
+
+
+def time_config1(torch, tess, B, wl, steps, warmup):
+    """Configuration 1: the whole [2,2,1] grid in fp32 on the plain fp32-FMA kernel, one
+    processor after the other on strided views of the global matrices (12 calls per step)."""
+    import itertools
+    from paper_2105_14500_amd import partition as P
+    w = wl.WORKLOADS[0]
+    L = w.layers[0]
+    q, d, a, b, c = w.q, w.d, L.a, L.b, L.c
+    X, W, bias, dY = (t.to("cuda:0") for t in wl.full_grid_inputs(a, b, c, dtype="f32", seed=0, bias_std=0.0))
+    Y = torch.empty((a, c), device="cuda:0")
+    dX = torch.empty((a, b), device="cuda:0")
+    dW = torch.zeros((b, c), device="cuda:0")
+    n = c // q
+    procs = []
+    for i, j, k in itertools.product(range(q), range(q), range(d)):
+        desc = B.make_desc(q, d, i, j, k, a, b, c, B.F32, B.F32)
+        procs.append((desc, P.fwd_panels(X, W, q, d, i, j, k), bias[j * n:(j + 1) * n], P.out_block(Y, q, d, i, j, k),
+                      P.dx_panels(dY, W, q, d, i, j, k), P.out_block(dX, q, d, i, j, k),
+                      P.dw_panels(X, dY, q, d, i, j, k), P.weight_block(dW, q, i, j)))
+
+    def step():
+        for desc, (ap, bp), bs, yo, (dyp, wp), dxo, (xp, dy2p), dwo in procs:
+            tess.linear_fwd(desc, ap, bp, bs, B.ACT_NONE, yo)
+            tess.linear_bwd_dx(desc, dyp, wp, dxo)
+            tess.linear_bwd_dw(desc, xp, dy2p, dwo, accumulate=True)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    flops = 6.0 * a * b * c
+    return {"tflops": round(flops / ms / 1e9, 3), "ms_per_step": round(ms, 4), "dtype": "f32",
+            "calls_per_step": 3 * len(procs), "kernel": "tess_generic_kernel (fp32 FMA)",
+            "roofline": {"bound": "alu", "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(flops / ms / 1e9 / PEAK_FP32_VECTOR_TFLOPS, 5)},
+            "note": "34 MFLOP per call: bound by launch latency, not by the ALUs"}
+
+
+def sustained(torch, step, flops_step, seconds=3.0):
+    """The same step looped for `seconds`: ms/step over the last second, with the shader clock
+    that rocm-smi reports sampled beside it (short bursts run at a higher clock than a
+    sustained load under the board's power limit)."""
+    import re
+    import subprocess
+    import threading
+    clocks, stop = [], threading.Event()
+
+    def sample():
+        while not stop.is_set():
+            try:
+                r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=5)
+                m = re.search(r"sclk clock level:\s*\d+:?\s*\((\d+)Mhz\)", r.stdout)
+                if m:
+                    clocks.append((time.perf_counter(), int(m.group(1))))
+            except Exception:
+                pass
+            stop.wait(0.25)
+
+    th = threading.Thread(target=sample, daemon=True)
+    th.start()
+    chunks, n = [], 0
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    while time.perf_counter() - t_start < seconds:
+        t0 = time.perf_counter()
+        for _ in range(20):
+            step(n)
+            n += 1
+        torch.cuda.synchronize()
+        chunks.append((time.perf_counter(), (time.perf_counter() - t0) / 20 * 1e3))
+    t_end = time.perf_counter()
+    stop.set()
+    th.join(timeout=6)
+    last = [ms for t, ms in chunks if t >= t_end - 1.0] or [chunks[-1][1]]
+    first = chunks[0][1]
+    ms_last = sum(last) / len(last)
+    sclk = [c for t, c in clocks if t >= t_end - 1.5 and t <= t_end]
+    return {"seconds": round(t_end - t_start, 2), "steps": n, "ms_per_step_first_chunk": round(first, 4),
+            "ms_per_step_last_second": round(ms_last, 4), "tflops_last_second": round(flops_step / ms_last / 1e9, 1),
+            "sclk_mhz_last_second": (round(sum(sclk) / len(sclk)) if sclk else None),
+            "sclk_source": "rocm-smi --showclocks, sampled every 0.25 s"}
 
 
 def main():
@@ -315,16 +407,23 @@ def main():
                                         for k, v in r["calls"].items()}}), flush=True)
             del r
         return
-    # what the matrix cores sustain on this device at its actual clock (no memory traffic)
+    # what the matrix cores sustain on this device at its actual clock (no memory traffic):
+    # with operands of small integers, and with operands distributed like the workload's --
+    # under the board's power limit the sustained clock depends on how much the operands switch
     sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda:0")
-    B.probe_mfma_rate(sink, 256, 2000)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    probe_flop = B.probe_mfma_rate(sink, 256, 20000)
-    e1.record()
-    torch.cuda.synchronize()
-    mfma_only = probe_flop / e0.elapsed_time(e1) / 1e9
+
+    def probe(real):
+        B.probe_mfma_rate(sink, 256, 1000, real_data=real)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = sum(B.probe_mfma_rate(sink, 256, 10000, real_data=real) for _ in range(3))
+        e1.record()
+        torch.cuda.synchronize()
+        return flop / e0.elapsed_time(e1) / 1e9
+
+    mfma_only = probe(False)
+    mfma_only_real = probe(True)
 
     res = time_workload(torch, tess, B, wl, w, args.steps, args.warmup)
     # dominant kernel = the call with the most flops that is ONE launch of the MFMA kernel
@@ -335,6 +434,8 @@ def main():
     layer_of = lambda name: next(st for st in res["layers"] if name.startswith(st.L.name + "."))
     dom_name = max(single, key=lambda name: layer_of(name).flops_call)
     dom, dom_layer = single[dom_name], layer_of(dom_name)
+    # HBM-side bytes per launch of that call: from the committed rocprofv3 counter summary (two
+    # --pmc runs of this script; counters cannot be read from inside the run)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_cfg4.txt")
     if os.path.exists(tpath):
@@ -352,7 +453,9 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "pct_of_bf16_mfma_peak": round(100.0 * res["tflops"] / PEAK_BF16_TFLOPS, 2),
         "mfma_only_loop_tflops": round(mfma_only, 1),
+        "mfma_only_loop_workload_like_operands_tflops": round(mfma_only_real, 1),
         "pct_of_mfma_only_loop": round(100.0 * res["tflops"] / mfma_only, 2),
+        "pct_of_mfma_only_loop_workload_like_operands": round(100.0 * res["tflops"] / mfma_only_real, 2),
         "config": {"workload": w.name, "grid": [w.q, w.q, w.d], "processor": [0, 0, 0],
                    "layers": {L.name: {"a": L.a, "b": L.b, "c": L.c, "block": [L.m, L.kb, L.n],
                                        "epilogue": L.act} for L in w.layers},
@@ -363,11 +466,20 @@ def main():
                      "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4),
                      "flop_per_launch": dom_layer.flops_call, "avg_ms": dom["ms"],
-                     "traffic": traffic,
-                     # context: the rate a register-resident MFMA-only loop reached in this run
+                     "avg_ms_median": dom["ms_median"], "avg_ms_min": dom["ms_min"],
+                     "traffic": traffic, "traffic_source": "profiles/hbm_traffic_cfg4.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)",
+                     # context: what a register-resident MFMA-only loop (no data movement at all)
+                     # reached in this run, on small-integer operands and on operands distributed
+                     # like the workload's: the second is the ceiling that the board's power
+                     # limit leaves to ANY kernel on this data
                      "mfma_only_loop": round(mfma_only, 1),
-                     "frac_of_mfma_only_loop": round(dom["tflops"] / mfma_only, 4)},
+                     "mfma_only_loop_workload_like_operands": round(mfma_only_real, 1),
+                     "frac_of_mfma_only_loop": round(dom["tflops"] / mfma_only, 4),
+                     "frac_of_mfma_only_loop_workload_like_operands": round(dom["tflops"] / mfma_only_real, 4)},
     }
+    if not args.no_sustained:
+        out["sustained"] = sustained(torch, res["step"], res["flops_step"], seconds=3.0)
+        out["sustained"]["pct_of_bf16_mfma_peak"] = round(100.0 * out["sustained"]["tflops_last_second"] / PEAK_BF16_TFLOPS, 2)
     if args.mlp_chain:
         by_name = {L.name: L for L in w.layers}
         if "up" not in by_name or "down" not in by_name:
@@ -414,33 +526,28 @@ def main():
                 ep[f"{st.L.name}.{fused}"] = {plain + "_ms": round(tp, 4), fused + "_ms": round(tf, 4)}
         out["backward_epilogues"] = ep
     layers0 = res["layers"]
-    if args.all:
+    if w.name == DEFAULT_WORKLOAD and not args.no_others:
+        # every other configuration rides along (per-call figures; panels drawn on the device
+        # with the same distributions, which takes seconds instead of minutes)
         others = {}
-        del res
+        res = None
         for ow in wl.WORKLOADS:
             if ow.dtype != "bf16" or ow.name == w.name:
                 continue
             torch.cuda.empty_cache()
-            r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup)
+            r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, on_device=True)
             others[ow.name] = {"tflops": round(r["tflops"], 2),
                                "pct_peak": round(100.0 * r["tflops"] / PEAK_BF16_TFLOPS, 2),
                                "ms_per_step": round(r["ms_per_step"], 4), "calls": r["calls"]}
             del r
-        out["other_workloads"] = others
-    elif w.name == DEFAULT_WORKLOAD:
-        # the small MLP up-projection configuration (launch-bound: 8.6 GFLOP per call) is cheap
-        # enough to ride along with every default run
+        # the small MLP up-projection replayed from a HIP graph: what is left once the
+        # per-launch host cost is gone
         ow = wl.workload_by_name("cfg2_q2d2_bf16_mlp_up_h1024")
-        r = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup)
-        out["other_workloads"] = {ow.name: {"tflops": round(r["tflops"], 2),
-                                            "pct_peak": round(100.0 * r["tflops"] / PEAK_BF16_TFLOPS, 2),
-                                            "ms_per_step": round(r["ms_per_step"], 4), "calls": r["calls"]}}
-        del r
-        # the same step replayed from a HIP graph: what is left once the per-launch host cost is gone
-        rg = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, graph=True)
-        out["other_workloads"][ow.name]["graph_replay"] = {"tflops": round(rg["tflops"], 2),
-                                                           "ms_per_step": round(rg["ms_per_step"], 4)}
+        rg = time_workload(torch, tess, B, wl, ow, args.steps, args.warmup, on_device=True, graph=True)
+        others[ow.name]["graph_replay"] = {"tflops": round(rg["tflops"], 2), "ms_per_step": round(rg["ms_per_step"], 4)}
         del rg
+        others[wl.WORKLOADS[0].name] = time_config1(torch, tess, B, wl, max(args.steps, 20), args.warmup)
+        out["other_workloads"] = others
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(torch, w, layers0[0])
     print(json.dumps(out))
