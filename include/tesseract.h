@@ -22,7 +22,7 @@
  *  - Ownership: the caller owns every buffer, including the workspace.  The
  *    library allocates nothing, keeps no state between calls (apart from having
  *    set a launch attribute of its kernels once per device) and never
- *    synchronises; kernels are enqueued on `hip_stream` (a hipStream_t cast to
+ *    synchronises; calls that share a workspace must be ordered (same stream); kernels are enqueued on `hip_stream` (a hipStream_t cast to
  *    void*, NULL = the default stream) of the current device.
  *  - Errors: a status code is returned, nothing is thrown or aborted.  All
  *    argument checks happen before the first HIP call, so they work on a
@@ -235,16 +235,14 @@ size_t tess_linear_workspace_bytes(const tess_desc* desc, int op);
 
 /* Launch shape that the call `op` would use for this descriptor: output macro tile and
  * number of K splits (1 = the whole q-step sum stays in one workgroup's registers; > 1 =
- * that many equal parts of the K range, partial sums go through the workspace and are
- * summed in ascending order before the epilogue; 0 = the two-level schedule, which only the
- * diagnostic override selects: one workgroup per compute unit, every tile's K range cut
- * into a main part and a tail, the tile completed by the last of its contributors to
- * finish, again in ascending K order).
- * tile 0 x 0 means the plain fp32 kernel: fp32 inputs, or a bf16 block
- * whose contiguous extents are no multiple of 8.  Pure host arithmetic.  A call whose
- * plan uses the matrix cores needs 16-byte aligned panel pointers and leading dimensions
- * that are multiples of 8 elements, and returns TESS_ERR_ALIGN otherwise (it never drops
- * to the plain kernel silently); a panel of 4 GiB or more returns TESS_ERR_UNSUPPORTED. */
+ * that many equal parts of the K range, whose partial sums go through the workspace and are
+ * added in ascending K order by a reduction kernel that applies the epilogue).  tile 0 x 0
+ * means the plain
+ * fp32 kernel: fp32 inputs, or a bf16 block whose contiguous extents are no multiple of 8.
+ * Pure host arithmetic.  A call whose plan uses the matrix cores needs 16-byte aligned
+ * panel pointers and leading dimensions that are multiples of 8 elements, and returns
+ * TESS_ERR_ALIGN otherwise (it never drops to the plain kernel silently); a panel of 4 GiB
+ * or more returns TESS_ERR_UNSUPPORTED. */
 tess_status tess_linear_plan(const tess_desc* desc, int op, int32_t* tile_m, int32_t* tile_n,
                              int32_t* k_splits);
 

@@ -31,18 +31,11 @@ tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, 
 tess_status tess_tile_of_block(int32_t block, int32_t tiles_m, int32_t tiles_n, int32_t* tm,
                                int32_t* tn);
 
-/* Forces the launch shape of every later call of this process, where the shape allows it:
- *   tile     : 128 or 256, 0 = cost model;
- *   k_splits : >= 1 = that many equal K parts with a reduction kernel, 0 = cost model;
- *   stream_k : >= 1 = the two-level schedule for launches of 128..248 tiles of 256 x 256 and
- *              at least 48 K stages (one workgroup per compute unit; on every XCD the main
- *              workgroups take the first part of one tile's K range each, in step, and
- *              the others share the tails; tiles are completed through the workspace by
- *              their last contributor); n >= 2 also sets the number of stages by which
- *              the tails are to finish ahead of the mains (default 16); 0 or -1 = off.
- * tess_linear_plan, tess_linear_workspace_bytes and the launches all see the same override.
- * Process-wide and not synchronised with running calls: for sweeps and tests. */
-tess_status tess_diag_set_plan_override(int32_t tile, int32_t k_splits, int32_t stream_k);
+/* Forces the macro tile (128 or 256; 0 = cost model) and the number of equal K parts (>= 1;
+ * 0 = cost model) of every later call of this process, where the shape allows them.
+ * tess_linear_plan, tess_linear_workspace_bytes and the launches all see the same
+ * override.  Process-wide and not synchronised with running calls: for sweeps and tests. */
+tess_status tess_diag_set_plan_override(int32_t tile, int32_t k_splits);
 
 #ifdef __cplusplus
 }

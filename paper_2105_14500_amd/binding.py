@@ -92,7 +92,7 @@ def lib():
         L.tess_probe_mfma_rate.restype = cint
         L.tess_probe_mfma_rate.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]
         L.tess_diag_set_plan_override.restype = cint
-        L.tess_diag_set_plan_override.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        L.tess_diag_set_plan_override.argtypes = [ctypes.c_int32, ctypes.c_int32]
         L.tess_tile_of_block.restype = cint
         L.tess_tile_of_block.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_int32)] * 2
         L.tess_desc_check.restype = cint
@@ -176,10 +176,9 @@ def probe_mfma_rate(sink, workgroups, iters, real_data=False, stream=None):
     return workgroups * 4 * iters * 16 * 32768.0
 
 
-def set_plan_override(tile=0, k_splits=0, stream_k=-1):
-    """tess_diag_set_plan_override: force tile (128/256), K splits and the stream-K schedule
-    (1 on, 0 off) of later calls; 0 / 0 / -1 = cost model."""
-    st = lib().tess_diag_set_plan_override(tile, k_splits, stream_k)
+def set_plan_override(tile=0, k_splits=0):
+    """tess_diag_set_plan_override: force tile (128/256) and K splits of later calls; 0 = cost model."""
+    st = lib().tess_diag_set_plan_override(tile, k_splits)
     if st:
         raise TessError(st, "tess_diag_set_plan_override")
 

@@ -6,28 +6,13 @@
 
 #include <atomic>
 #include <mutex>
-#include <random>
 
 namespace tess {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Tuning overrides of the diagnostic interface (0 / -1 = the cost model decides).
-static std::atomic<int> g_force_tile{0}, g_force_splits{0}, g_force_streamk{-1};
-
-// Tag of a stream-K call's control words: unique per call within the process, 48 bits,
-// never zero, started from a random value so that words left in a workspace by another
-// process do not match either.
-static unsigned long long next_token()
-{
-    static std::atomic<unsigned long long> counter{[] {
-        std::random_device rd;
-        return ((unsigned long long)rd() << 32) ^ rd();
-    }()};
-    unsigned long long t;
-    do { t = counter.fetch_add(1, std::memory_order_relaxed) & 0xffffffffffffull; } while (t == 0);
-    return t;
-}
+// Tuning overrides of the diagnostic interface (0 = the cost model decides).
+static std::atomic<int> g_force_tile{0}, g_force_splits{0};
 
 // Shape-only part of the plan (what tess_linear_workspace_bytes can know).  a_kc / b_kc:
 // operand orientation of the call (see GemmArgs).
@@ -38,8 +23,6 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16, bo
     p.bm = p.bn = 0;
     p.splits = 1;
     p.direct = 0;
-    p.sk_workers = 0;
-    p.sk_main = 0;
     p.ws_bytes = 0;
     if (!in_bf16) return p;
     // the matrix-core path moves 16-byte granules (8 bf16) along the contiguous index of
@@ -58,28 +41,7 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16, bo
     const TileCost cands[2] = {{256, 10.0, 1.0, 1.6}, {128, 5.0, 0.36, 0.60}};
     const double kLaunchUs = 4.0, kReduceLaunchUs = 2.0, kReduceBytesPerUs = 4.0e6;
     const int kCU = 256;
-    // Two-level schedule for tile counts between half and all of the compute units (one
-    // workgroup per compute unit): per XCD, n tiles get a main workgroup each for the first
-    // `main` K stages and the other 32 - n workgroups share the tails.  `main` balances the
-    // two kinds of workgroup and lets the tails finish `lead` stages early, so that a main
-    // workgroup finds the tail's partial sum waiting when it completes the tile.  Measured on
-    // MI355X it only ties with the best equal split (the board is power-bound: compute units
-    // that the plain launch leaves idle raise the clock of the busy ones), so the cost model
-    // never picks it; the diagnostic override does.
-    auto twolevel_main = [&](int t, int lead) {
-        const int64_t tiles = ((M + t - 1) / t) * ((N + t - 1) / t);
-        const int n = (int)((tiles + 7) / 8), tails = 32 - n;
-        int64_t a = ((int64_t)n * kt_total + (int64_t)lead * tails + 31) / 32;
-        if (a > kt_total - 8) a = kt_total - 8;
-        return (int)a;
-    };
-    auto twolevel_ok = [&](int t) {
-        const int64_t tiles = ((M + t - 1) / t) * ((N + t - 1) / t);
-        return t == 256 && p.direct && M >= 256 && N >= 256 && tiles >= kCU / 2 && tiles <= kCU - 8 && kt_total >= 48;
-    };
-    const int kLeadStages = 16;
     double best = 1e30;
-    bool best_sk = false;
     for (int ci = 0; ci < 2; ++ci) {
         const TileCost& tc = cands[ci];
         const int t = tc.t;
@@ -98,27 +60,13 @@ static Plan shape_plan(int64_t M, int64_t N, int64_t Kp, int q, bool in_bf16, bo
             }
             if (sp > 1)
                 cost += kReduceLaunchUs + (double)wgs * t * t * sizeof(float) / kReduceBytesPerUs;
-            if (cost < best) { best = cost; p.bm = p.bn = t; p.splits = sp; best_sk = false; }
+            if (cost < best) { best = cost; p.bm = p.bn = t; p.splits = sp; }
         }
     }
     // tuning overrides of the diagnostic interface; the workspace query, the plan query and
     // the launch all pass through here, so they agree
     if (const int v = g_force_tile.load(std::memory_order_relaxed)) { if (v == 128 || (v == 256 && p.direct && M >= 256 && N >= 256)) p.bm = p.bn = v; }
-    if (const int v = g_force_splits.load(std::memory_order_relaxed)) { if (v >= 1 && kt_total / v >= 1) { p.splits = v; best_sk = false; } }
-    int lead = kLeadStages;
-    {
-        const int v = g_force_streamk.load(std::memory_order_relaxed);
-        if (v == 0) best_sk = false;
-        if (v >= 1 && twolevel_ok(p.bm)) { best_sk = true; p.splits = 1; if (v >= 2) lead = v; }
-    }
-    if (best_sk) {
-        const int64_t tiles = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
-        p.sk_workers = kCU;
-        p.sk_main = twolevel_main(p.bm, lead);
-        p.splits = 0;
-        p.ws_bytes = sk_head_bytes(tiles) + (size_t)kSkSlots * sk_slot_bytes(p.bm, p.bn);
-        return p;
-    }
+    if (const int v = g_force_splits.load(std::memory_order_relaxed)) { if (v >= 1 && kt_total / v >= 1) { p.splits = v; } }
     const int64_t tiles = ((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
     if (p.splits > 1)
         p.ws_bytes = (size_t)p.splits * tiles * p.bm * p.bn * sizeof(float) +
@@ -177,15 +125,6 @@ static tess_status run(GemmArgs& g, void* workspace, size_t workspace_bytes, voi
         if (!workspace || workspace_bytes < p.ws_bytes) return TESS_ERR_WORKSPACE;
         if (reinterpret_cast<uintptr_t>(workspace) & 255u) return TESS_ERR_WORKSPACE;
         g.ws = static_cast<float*>(workspace);
-    }
-    if (p.sk_workers > 0) {
-        const int64_t tiles = ((g.M + p.bm - 1) / p.bm) * (int64_t)((g.N + p.bn - 1) / p.bn);
-        char* base = static_cast<char*>(workspace);
-        g.sk_ctrl = reinterpret_cast<unsigned long long*>(base);
-        g.sk_flags = g.sk_ctrl + tiles;
-        g.ws = reinterpret_cast<float*>(base + sk_head_bytes(tiles));
-        g.sk_main = p.sk_main;
-        g.sk_token = next_token();
     }
 #ifdef TESS_STAMPS
     // diagnostic build: the time stamps follow the workspace proper (the caller leaves 1 MiB of room)
@@ -541,13 +480,11 @@ tess_status tess_probe_mfma_rate(void* sink, int32_t workgroups, int32_t iters, 
     return e == hipSuccess ? TESS_OK : TESS_ERR_HIP;
 }
 
-tess_status tess_diag_set_plan_override(int32_t tile, int32_t k_splits, int32_t stream_k)
+tess_status tess_diag_set_plan_override(int32_t tile, int32_t k_splits)
 {
     if ((tile != 0 && tile != 128 && tile != 256) || k_splits < 0 || k_splits > 64) return TESS_ERR_UNSUPPORTED;
-    if (stream_k < -1 || stream_k > 256 || (stream_k >= 1 && k_splits > 1)) return TESS_ERR_UNSUPPORTED;
     g_force_tile.store(tile, std::memory_order_relaxed);
     g_force_splits.store(k_splits, std::memory_order_relaxed);
-    g_force_streamk.store(stream_k, std::memory_order_relaxed);
     return TESS_OK;
 }
 

@@ -46,14 +46,6 @@ struct GemmArgs {
     // followed by splits x N partial column sums
     int32_t splits;
     float* ws;
-    // two-level schedule of the STREAMK kernels (256 workgroups, see tess_mfma_kernel): the
-    // first sk_main K stages of a tile belong to its main workgroup, the rest to the tail
-    // workgroups of the tile's XCD.  ws then holds 64 partial slots per XCD, sk_flags one
-    // word per slot, sk_ctrl one word per tile.
-    int32_t sk_main;
-    unsigned long long sk_token;     // tag of this call's control words (48 bits, non-zero)
-    unsigned long long* sk_ctrl;
-    unsigned long long* sk_flags;
     unsigned long long* stamps;      // diagnostic builds only (TESS_STAMPS): 16 time stamps per workgroup
 };
 
@@ -107,17 +99,8 @@ struct Plan {
     int32_t bm, bn;     // macro tile of the MFMA path
     int32_t splits;     // K splits (1 = none): equal parts over gridDim.z + reduction kernel
     int32_t direct;     // 1: global->LDS direct loads (needs Kp % 64 == 0)
-    int32_t sk_workers; // > 0: two-level (main + tails) schedule with this many workgroups (256) ...
-    int32_t sk_main;    // ... and this many K stages of every tile done by its main workgroup
     size_t ws_bytes;
 };
-
-// Workspace layout of the two-level schedule: control words (one per tile), flags (one per
-// partial slot), both 8 bytes, padded to 256 bytes; then 64 partial slots per XCD, each a
-// BM x BN fp32 tile in row order + 1 KiB of partial column sums.
-constexpr int kSkSlots = 8 * 64;
-inline size_t sk_slot_bytes(int bm, int bn) { return (size_t)bm * bn * 4 + 1024; }
-inline size_t sk_head_bytes(int64_t tiles) { return ((size_t)(tiles + kSkSlots) * 8 + 255) & ~(size_t)255; }
 
 // Enqueue; returns hipSuccess or the launch error.
 hipError_t launch_generic(const GemmArgs& g, hipStream_t s);

@@ -523,11 +523,8 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
 // fp32 accumulation, issued in the shadow of the MFMAs.  (An extra MFMA with an all-ones
 // A fragment would need accumulator registers that the tile already uses up: the
 // compiler then copies 16 registers in and out around every such MFMA.)
-// STREAMK: the workgroup walks a list of segments (see below) and fixes shared tiles up
-// through the workspace; compiled as kernels of their own so that the one-tile-per-workgroup
-// kernels keep their register allocation (the segment loop costs spills outside the K loop).
 template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT,
-          bool COLSUM = false, bool STREAMK = false>
+          bool COLSUM = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
 {
     constexpr int NT = 64 * WGM * WGN;
@@ -549,42 +546,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     const int kt_per_panel = (g.Kp + BK - 1) / BK;
     const int kt_total = g.q * kt_per_panel;
 
-    // ---- work of this workgroup: a list of segments (output tile, range of K stages).
-    // One tile per workgroup, whole K or one of gridDim.z equal parts of it; or the
-    // two-level schedule (STREAMK) for tile counts between half and all of the compute
-    // units, one workgroup per compute unit: on every XCD (32 workgroups, n_x tiles that
-    // are consecutive in the tile order) n_x "main" workgroups take the first g.sk_main
-    // stages of one tile each, in step with each other so that they share panels in the
-    // L2 as the one-tile-per-workgroup launch does, and the remaining 32 - n_x workgroups
-    // share the tiles' remaining stages ("tails") as one sequence of (tile, stage) units.
-    // A tile is completed by whichever of its contributors finishes last (see below).
-    constexpr bool streamk = STREAMK;
-    int sk_xcd = 0, sk_i = 0, sk_nx = 0, sk_first = 0;   // XCD, index on it, its tiles: count and first
-    int sk_upw = 0, sk_L = 0;                             // tail units per tail workgroup, tail length
-    int sk_u = 0, sk_uend = 0;                            // units still to do (tail workgroups)
-    bool sk_main_todo = false;
-    if constexpr (STREAMK) {
-        sk_xcd = blockIdx.x & 7;
-        sk_i = blockIdx.x >> 3;
-        const int per = nb >> 3, rem = nb & 7;
-        sk_nx = per + (sk_xcd < rem ? 1 : 0);
-        sk_first = sk_xcd * per + (sk_xcd < rem ? sk_xcd : rem);
-        sk_L = kt_total - g.sk_main;
-        const int tails = 32 - sk_nx;
-        sk_upw = (sk_nx * sk_L + tails - 1) / tails;
-        if (sk_i < sk_nx) {
-            sk_main_todo = true;
-        } else {
-            sk_u = (sk_i - sk_nx) * sk_upw;
-            sk_uend = sk_u + sk_upw < sk_nx * sk_L ? sk_u + sk_upw : sk_nx * sk_L;
-        }
-    }
-    // the segment being computed
+    // ---- work of this workgroup: one output tile and a range of K stages: the whole K
+    // loop, or one of g.splits equal parts of it (over gridDim.z, with the reduction kernel
+    // behind the launch)
     int tm = 0, tn = 0, row0 = 0, col0 = 0, kt_begin = 0, nkt = 0;
-    int sk_tl = 0;                  // the tile's index among its XCD's tiles
-#ifdef TESS_STAMPS
-    int seg = -1;
-#endif
 
     typedef DmaLoader<BM, BK, A_KC, NT> LA;
     typedef DmaLoader<BN, BK, B_KC, NT> LB;
@@ -725,37 +690,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
 
-    for (;;) {
-        // ---- next segment
-        if constexpr (STREAMK) {
-            if (sk_main_todo) {
-                sk_main_todo = false;
-                sk_tl = sk_i;
-                kt_begin = 0;
-                nkt = g.sk_main;
-            } else {
-                if (sk_u >= sk_uend) break;
-                sk_tl = sk_u / sk_L;
-                const int at = sk_u - sk_tl * sk_L;
-                kt_begin = g.sk_main + at;
-                nkt = sk_uend - sk_u < sk_L - at ? sk_uend - sk_u : sk_L - at;
-                sk_u += nkt;
-            }
-            tile_of_index(sk_first + sk_tl, tiles_m, tiles_n, nb >> 3, tm, tn);
-        } else {
-            tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
-            kt_begin = 0;
-            nkt = kt_total;
-            if (g.splits > 1) {
-                const int z = blockIdx.z;
-                const int base = kt_total / g.splits, extra = kt_total % g.splits;
-                kt_begin = z * base + (z < extra ? z : extra);
-                nkt = base + (z < extra ? 1 : 0);
-            }
+    {
+        tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
+        kt_begin = 0;
+        nkt = kt_total;
+        if (g.splits > 1) {
+            const int z = blockIdx.z;
+            const int base = kt_total / g.splits, extra = kt_total % g.splits;
+            kt_begin = z * base + (z < extra ? z : extra);
+            nkt = base + (z < extra ? 1 : 0);
         }
-#ifdef TESS_STAMPS
-        ++seg;
-#endif
         row0 = tm * BM;
         col0 = tn * BN;
         ld_t = kt_begin / kt_per_panel;
@@ -789,7 +733,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
                 static_for<FIRST>([&](auto it) { request(it); });
                 wait_vmcnt<(NSTAGE - 2) * LOADS + FIRST>();            // tile 0 has landed
                 lds_barrier();
-                TESS_STAMP(1 + 4 * seg);
+                TESS_STAMP(1);
                 load_frags(std::integral_constant<int, 0>{}, 0, std::integral_constant<int, 0>{});
             }
             int stage = 0;
@@ -803,7 +747,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
                 last_step(next, yes, yes);
                 stage = next;
             }
-            TESS_STAMP(2 + 4 * seg);
+            TESS_STAMP(2);
             // the epilogue reuses the LDS: nothing may still be landing in it
             wait_vmcnt<0>();
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -843,24 +787,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             }
         }
 
-        // ---- finish the segment
-        // Lane and wavefront ids as this iteration's own values: what the code below derives
-        // from them (hundreds of LDS and output offsets) is the same for every segment, and
-        // the compiler would otherwise compute all of it before the segment loop and keep it
-        // in registers through the K loop, at the price of spills inside that loop.
-        int elane = lane, ewave = wave;
-        if constexpr (STREAMK) asm volatile("" : "+v"(elane), "+v"(ewave));
-        const int ewm = ewave / WGN, ewn = ewave % WGN;
-        // column sums of the segment: elane l holds column l % 32 of each fragment for the
+        // ---- finish
+        const int elane = lane, ewave = wave, ewm = wm, ewn = wn;
+        // column sums of this K range: lane l holds column l % 32 of each fragment for the
         // k-values 8 (l / 32) .. + 7 of every k16 step, so the two halves of the wavefront
         // add up to the column sum (valid in lanes 0..31)
         float csv[COLSUM ? FN : 1];
         if constexpr (COLSUM) {
             static_for<FN>([&](auto j) { csv[j] = cs[j] + __shfl_xor(cs[j], 32, 64); });
         }
-        if (!streamk && g.splits > 1) {
+        if (g.splits > 1) {
             // equal K parts over gridDim.z: partial sums in accumulator order
-            // [(z*nb + tile)][ewave][frag][reg][elane] for the reduction kernel
+            // [(z*nb + tile)][wave][frag][reg][lane] for the reduction kernel
             if constexpr (COLSUM) {
                 if (cs_wave) {
                     float* part = g.ws + (size_t)g.splits * nb * (BM * BN) + (size_t)blockIdx.z * g.N;
@@ -877,270 +815,123 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
                 __builtin_amdgcn_sched_barrier(0);
             });
 #ifdef TESS_STAMPS
-            wait_vmcnt<0>(); TESS_STAMP(4 + 4 * seg);
+            wait_vmcnt<0>(); TESS_STAMP(4);
 #endif
-            break;
-        }
-        // ---- shared tiles (STREAMK).  The tile's P contributors -- the main workgroup
-        // (p = 0) and the tail workgroups that hold parts of its tail, in ascending K order --
-        // announce themselves on the tile's control word as they finish.  All but the last
-        // to arrive write their accumulators, as an fp32 tile in row order, to their partial
-        // slot and then raise the slot's flag.  The last one waits for those flags (their
-        // owners have arrived already and only have the write left: the wait is short and
-        // never depends on a workgroup that has not started), adds the partials to its own
-        // sum IN ASCENDING K ORDER, its own contribution at its place, and runs the epilogue.
-        // Words carry the call's token, so that whatever an earlier call or another user of
-        // the memory left there reads as "nobody yet"; the last arrival puts the words it
-        // used back to that state (a replayed graph passes the same token again).  Partials
-        // are written through and read past the per-XCD L2 (sc1), flags and control words
-        // are agent-scope atomics: no cache-wide write-back or invalidate is involved.
-        constexpr int SC1 = 16;
-        constexpr uint32_t SLOT_BYTES = BM * BN * 4 + 1024;
-        int P = 1, mine = 0, sk_jf = 0;
-        bool writer = false;
-        auto slot_index = [&](int p) {
-            // 64 slots per XCD: 0..31 the tails' (tile + tail workgroup, a chain without repeats), 32.. the mains'
-            return sk_xcd * 64 + (p == 0 ? 32 + sk_tl : sk_tl + sk_jf + p - 1);
-        };
-        auto slot_rsrc = [&](int p) {
-            char* base = (char*)g.ws + (size_t)slot_index(p) * SLOT_BYTES;
-            return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)SLOT_BYTES, 0x00020000);
-        };
-        if constexpr (STREAMK) {
-            sk_jf = (sk_tl * sk_L) / sk_upw;
-            const int jl = ((sk_tl + 1) * sk_L - 1) / sk_upw;
-            P = 2 + jl - sk_jf;
-            mine = kt_begin == 0 ? 0 : 1 + (sk_i - sk_nx) - sk_jf;
-            volatile int* sh = (volatile int*)lds;
-            if (tid == 0) {
-                unsigned long long* ctrl = g.sk_ctrl + (sk_first + sk_tl);
-                unsigned long long old = __hip_atomic_load(ctrl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                unsigned long long des;
-                do {
-                    des = ((old >> 16) == g.sk_token ? old : (g.sk_token << 16)) + 1;
-                } while (!__hip_atomic_compare_exchange_strong(ctrl, &old, des, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT));
-                const int arrival = (int)(des & 0xffffu);          // 1 .. P
-                int bad = 0;
-                if (arrival == P) {
-                    for (int p = 0; p < P; ++p) {
-                        if (p == mine) continue;
-                        unsigned long long* f = g.sk_flags + slot_index(p);
-                        int spins = 0;
-                        while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != g.sk_token) {
-                            if (++spins > (1 << 22)) { bad = 1; break; }      // bounded: never hang the device
-                            __builtin_amdgcn_s_sleep(8);
-                        }
-                        __hip_atomic_store(f, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                    __hip_atomic_store(ctrl, g.sk_token << 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                sh[0] = arrival;
-                sh[1] = bad;
-            }
-            lds_barrier();
-            writer = __builtin_amdgcn_readfirstlane(sh[0]) < P;
-            if (__builtin_amdgcn_readfirstlane(sh[1])) {
-                // a contributor never delivered (cannot happen on a healthy device): poison
-                // the tile rather than pass off a partial sum as the result
-                static_for<FM * FN>([&](auto x) { static_for<16>([&](auto r) { acc[x][r()] = __builtin_nanf(""); }); });
-            }
-            lds_barrier();                             // the words are overwritten below
-            // partial column sums travel in the last KiB of the slot
-            if constexpr (COLSUM) {
-                if (cs_wave && elane < 32) {
-                    const uint32_t tail_off = (uint32_t)(BM * BN * 4 + (ewn * WTN + elane) * 4);
-                    if (writer) {
-                        const auto rs = slot_rsrc(mine);
-                        static_for<FN>([&](auto j) {
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(csv[j]), rs, tail_off + j * 128, 0, SC1);
-                        });
-                    } else {
-                        static_for<FN>([&](auto j) {
-                            float run = 0.0f;
-                            for (int p = 0; p < P; ++p) {
-                                float v = csv[j];
-                                if (p != mine)
-                                    v = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(slot_rsrc(p), tail_off + j * 128, 0, SC1));
-                                run = p == 0 ? v : run + v;
-                            }
-                            csv[j] = run;
-                        });
-                    }
-                }
-            }
-        }
-        TESS_STAMP(3 + 4 * seg);
-        if constexpr (COLSUM) {
-            if (cs_wave && !writer) {
-                static_for<FN>([&](auto j) {
-                    const int col = col0 + ewn * WTN + j * 32 + elane;
-                    if (elane < 32 && col < g.N) g.colsum[col] = g.accumulate ? g.colsum[col] + csv[j] : csv[j];
-                });
-            }
+            return;
         }
         // ---- epilogue.  The wavefront passes its accumulators through a private slice of
         // the (now idle) LDS, half of its tile at a time, to turn the MFMA fragment layout
-        // into rows: a short rolled loop then handles four adjacent columns per lane, so
-        // every output row leaves as one contiguous run and the code stays small.
-        {
-            constexpr int HR = WTM / 2;                    // rows per half
-            constexpr int ROWB = WTN * 4;                  // fp32 bytes per row of the wave tile
-            constexpr int CPR = WTN / 4;                   // 16-byte chunks per row
-            constexpr int RPI = 64 / CPR;                  // rows per 64-lane pass
-            static_assert(FM % 2 == 0, "two halves of whole fragments");
-            static_assert(NSTAGE * STAGE_BYTES >= WGM * WGN * HR * ROWB, "LDS holds half a tile in fp32");
-            char* slice = lds + ewave * (HR * ROWB);
-            const int esize = g.out_f32 ? 4 : 2;
-            const bool vec = ((g.ldo * esize) % 16 == 0) &&
-                             ((reinterpret_cast<uintptr_t>(g.out) & 15u) == 0) &&
-                             (!g.preact || (reinterpret_cast<uintptr_t>(g.preact) & 15u) == 0) &&
-                             (!g.zin || (((reinterpret_cast<uintptr_t>(g.zin) & 7u) == 0) && (g.ldz % 4 == 0)));
-            // chunk c of row r is kept at chunk c ^ (8 * bit 2 of r): the two half-waves of
-            // a fragment (rows r and r+4) then write to different banks
-            constexpr int NIT = HR / RPI;                  // passes of the drain loop per half
-            // dX through GELU': the pre-activations are fetched before the accumulators are staged,
-            // so that their latency is hidden behind the LDS traffic instead of sitting in the loop
-            const bool dgelu = !writer && g.zin && g.dact == TESS_ACT_GELU_ERF && !g.out_f32 && !g.in_f32 &&
-                               !g.preact && g.act == TESS_ACT_NONE;
-            static_for<2>([&](auto half) {
-                const int wrow0 = row0 + ewm * WTM + half * HR, wcol0 = col0 + ewn * WTN;
-                // a lane serves the same four columns in every pass
-                const int c = elane % CPR, col = wcol0 + c * 4;
-                // byte offset, inside a partial slot, of this lane's four columns in pass 0
-                const uint32_t poff = (uint32_t)(((ewm * WTM + half * HR + elane / CPR) * BN + ewn * WTN + c * 4) * 4);
-                u32x2 zr[NIT];
-                if (dgelu) {
-                    static_for<NIT>([&](auto it) {
-                        const int row = wrow0 + it * RPI + elane / CPR;
-                        zr[it] = u32x2{0u, 0u};
-                        if (row < g.M && col < g.N) {
-                            const uint16_t* zp = (const uint16_t*)g.zin + (int64_t)row * g.ldz + col;
-                            if (vec && col + 3 < g.N) {
-                                zr[it] = *(const u32x2*)zp;
-                            } else {
-                                for (int e = 0; e < 4; ++e)
-                                    if (col + e < g.N) zr[it][e >> 1] |= (uint32_t)zp[e] << (16 * (e & 1));
-                            }
-                        }
+        // into rows: a short loop then handles four adjacent columns per lane (pass `it`
+        // serves rows it * RPI + lane / CPR of the half), so every output row leaves as one
+        // contiguous run and the code stays small.
+        constexpr int HR = WTM / 2;                    // rows per half
+        constexpr int ROWB = WTN * 4;                  // fp32 bytes per row of the wave tile
+        constexpr int CPR = WTN / 4;                   // 16-byte chunks per row
+        constexpr int RPI = 64 / CPR;                  // rows per 64-lane pass
+        constexpr int NIT = HR / RPI;                  // passes per half
+        static_assert(FM % 2 == 0, "two halves of whole fragments");
+        static_assert(NSTAGE * STAGE_BYTES >= WGM * WGN * HR * ROWB, "LDS holds half a tile in fp32");
+        char* slice = lds + ewave * (HR * ROWB);
+        const int esize = g.out_f32 ? 4 : 2;
+        const bool vec = ((g.ldo * esize) % 16 == 0) &&
+                         ((reinterpret_cast<uintptr_t>(g.out) & 15u) == 0) &&
+                         (!g.preact || (reinterpret_cast<uintptr_t>(g.preact) & 15u) == 0) &&
+                         (!g.zin || (((reinterpret_cast<uintptr_t>(g.zin) & 7u) == 0) && (g.ldz % 4 == 0)));
+        // a lane serves the same four columns in every pass
+        const int c = elane % CPR, wcol0 = col0 + ewn * WTN, col = wcol0 + c * 4;
+        // accumulators of one half -> the wavefront's LDS slice.  Chunk c of row r is kept at
+        // chunk c ^ (8 * bit 2 of r): the two half-waves of a fragment (rows r and r+4) then
+        // write to different banks
+        auto stage_half = [&](auto half) {
+            static_for<FM / 2>([&](auto ii) {
+                static_for<FN>([&](auto j) {
+                    constexpr int f = (half * (FM / 2) + ii) * FN + j;
+                    const int cl = j * 32 + (elane & 31);
+                    static_for<16>([&](auto r) {
+                        const int rl = ii * 32 + 8 * (r / 4) + 4 * (elane >> 5) + (r % 4);
+                        const int phys = (cl >> 2) ^ (((rl >> 2) & 1) << 3);
+                        *(float*)(slice + rl * ROWB + phys * 16 + (cl & 3) * 4) = acc[f][r()];
                     });
-                }
-                // the other contributor's half tile of a tile shared by two (the usual case) is
-                // fetched before the accumulators are staged, like the pre-activations above
-                floatx4 pv[STREAMK ? NIT : 1];
-                const bool fold2 = STREAMK && !writer && P == 2;
-                if constexpr (STREAMK) {
-                    if (fold2) {
-                        const auto rs = slot_rsrc(1 - mine);
-                        static_for<NIT>([&](auto it) {
-                            pv[it] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs, poff, it * (RPI * BN * 4), SC1));
-                        });
-                    }
-                }
-                static_for<FM / 2>([&](auto ii) {
-                    static_for<FN>([&](auto j) {
-                        constexpr int f = (half * (FM / 2) + ii) * FN + j;
-                        const int cl = j * 32 + (elane & 31);
-                        static_for<16>([&](auto r) {
-                            const int rl = ii * 32 + 8 * (r / 4) + 4 * (elane >> 5) + (r % 4);
-                            const int phys = (cl >> 2) ^ (((rl >> 2) & 1) << 3);
-                            *(float*)(slice + rl * ROWB + phys * 16 + (cl & 3) * 4) = acc[f][r()];
-                        });
-                        __builtin_amdgcn_sched_barrier(0);
-                    });
+                    __builtin_amdgcn_sched_barrier(0);
                 });
-                if constexpr (STREAMK) {
-                    if (writer) {
-                        // this contribution as it stands (no bias, no activation), to its slot
-                        const auto rs = slot_rsrc(mine);
-    #pragma unroll 4
-                        for (int it = 0; it < NIT; ++it) {
-                            const int rl = it * RPI + elane / CPR;
-                            const int phys = c ^ (((rl >> 2) & 1) << 3);
-                            const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
-                            if (wrow0 + rl < g.M && col < g.N)
-                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs, poff, it * (RPI * BN * 4), SC1);
-                        }
-                        return;
-                    }
-                    if (fold2) {
-                        // two contributions: the sum does not depend on the order
-                        static_for<NIT>([&](auto it) {
-                            const int rl = it * RPI + elane / CPR;
-                            const int phys = c ^ (((rl >> 2) & 1) << 3);
-                            floatx4* q = (floatx4*)(slice + rl * ROWB + phys * 16);
-                            if (wrow0 + rl < g.M && col < g.N) *q = *q + pv[it];
-                        });
-                    } else if (P > 2) {
-                        // three or more: ascending K order, this workgroup's own sum at its place
-                        for (int it = 0; it < NIT; ++it) {
-                            const int rl = it * RPI + elane / CPR;
-                            const int phys = c ^ (((rl >> 2) & 1) << 3);
-                            floatx4* q = (floatx4*)(slice + rl * ROWB + phys * 16);
-                            if (wrow0 + rl < g.M && col < g.N) {
-                                floatx4 run = {0.f, 0.f, 0.f, 0.f};
-                                for (int p = 0; p < P; ++p) {
-                                    floatx4 v = *q;
-                                    if (p != mine)
-                                        v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                                            slot_rsrc(p), poff, it * (RPI * BN * 4), SC1));
-                                    run = p == 0 ? v : run + v;
-                                }
-                                *q = run;
-                            }
-                        }
-                    }
-                }
-                // fetch the bias of the lane's four columns once
-                floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
-                if (g.bias) {
-    #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (col + e < g.N) bias4[e] = bf16_bits_to_f32(((const uint16_t*)g.bias)[col + e]);
-                }
-                auto drain = [&](auto mode) {
-    #pragma unroll 4
-                    for (int it = 0; it < NIT; ++it) {
-                        const int rl = it * RPI + elane / CPR;
-                        const int phys = c ^ (((rl >> 2) & 1) << 3);
-                        const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
-                        const int row = wrow0 + rl;
-                        if (row < g.M && col < g.N) emit4<mode>(g, row, col, v, bias4, vec);
-                    }
-                };
-                if (dgelu) {
-                    static_for<NIT>([&](auto it) {
-                        const int rl = it * RPI + elane / CPR;
-                        const int phys = c ^ (((rl >> 2) & 1) << 3);
-                        const floatx4 v = *(const floatx4*)(slice + rl * ROWB + phys * 16);
-                        const int row = wrow0 + rl;
-                        if (row < g.M && col < g.N) emit4<MODE_BF16_DGELU>(g, row, col, v, bias4, vec, zr[it]);
-                    });
-                }
-                else if (g.preact && !g.zin && !g.out_f32 && g.act == TESS_ACT_GELU_ERF)
-                    drain(std::integral_constant<int, MODE_BF16_GELU_PRE>{});
-                else if (g.zin || g.preact || g.act == TESS_ACT_GELU_TANH || (g.out_f32 && g.act != TESS_ACT_NONE))
-                    drain(std::integral_constant<int, MODE_GENERIC>{});
-                else if (g.out_f32 && g.accumulate) drain(std::integral_constant<int, MODE_F32_ACC>{});
-                else if (g.out_f32) drain(std::integral_constant<int, MODE_F32>{});
-                else if (g.act == TESS_ACT_GELU_ERF) drain(std::integral_constant<int, MODE_BF16_GELU>{});
-                else drain(std::integral_constant<int, MODE_BF16>{});
-                __builtin_amdgcn_sched_barrier(0);
             });
-            if constexpr (STREAMK) {
-                if (writer) {
-                    wait_vmcnt<0>();                   // every store of this wavefront is acknowledged
-                    lds_barrier();                     // ... and of the others
-                    if (tid == 0)
-                        __hip_atomic_store(g.sk_flags + slot_index(mine), g.sk_token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+        };
+        auto staged = [&](int it) -> floatx4* {     // the lane's four columns of pass `it`
+            const int rl = it * RPI + elane / CPR;
+            const int phys = c ^ (((rl >> 2) & 1) << 3);
+            return (floatx4*)(slice + rl * ROWB + phys * 16);
+        };
+        // fetch the bias of the lane's four columns once
+        floatx4 bias4 = {0.f, 0.f, 0.f, 0.f};
+        if (g.bias) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < g.N) bias4[e] = bf16_bits_to_f32(((const uint16_t*)g.bias)[col + e]);
+        }
+        // the drain mode of this call
+        const bool generic = g.zin || g.act == TESS_ACT_GELU_TANH || (g.out_f32 && (g.act != TESS_ACT_NONE || g.preact)) ||
+                             (g.preact && g.act != TESS_ACT_GELU_ERF);
+        auto with_mode = [&](auto&& body) {
+            if (generic) body(std::integral_constant<int, MODE_GENERIC>{});
+            else if (g.preact) body(std::integral_constant<int, MODE_BF16_GELU_PRE>{});
+            else if (g.out_f32 && g.accumulate) body(std::integral_constant<int, MODE_F32_ACC>{});
+            else if (g.out_f32) body(std::integral_constant<int, MODE_F32>{});
+            else if (g.act == TESS_ACT_GELU_ERF) body(std::integral_constant<int, MODE_BF16_GELU>{});
+            else body(std::integral_constant<int, MODE_BF16>{});
+        };
+
+        if constexpr (COLSUM) {
+            if (cs_wave) {
+                static_for<FN>([&](auto j) {
+                    const int ccol = col0 + ewn * WTN + j * 32 + elane;
+                    if (elane < 32 && ccol < g.N) g.colsum[ccol] = g.accumulate ? g.colsum[ccol] + csv[j] : csv[j];
+                });
             }
         }
+        // dX through GELU': the pre-activations are fetched before the accumulators are staged,
+        // so that their latency is hidden behind the LDS traffic instead of sitting in the loop
+        const bool dgelu = g.zin && g.dact == TESS_ACT_GELU_ERF && !g.out_f32 && !g.in_f32 &&
+                           !g.preact && g.act == TESS_ACT_NONE;
+        static_for<2>([&](auto half) {
+            const int wrow0 = row0 + ewm * WTM + half * HR;
+            u32x2 zr[NIT];
+            if (dgelu) {
+                static_for<NIT>([&](auto it) {
+                    const int row = wrow0 + it * RPI + elane / CPR;
+                    zr[it] = u32x2{0u, 0u};
+                    if (row < g.M && col < g.N) {
+                        const uint16_t* zp = (const uint16_t*)g.zin + (int64_t)row * g.ldz + col;
+                        if (vec && col + 3 < g.N) {
+                            zr[it] = *(const u32x2*)zp;
+                        } else {
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < g.N) zr[it][e >> 1] |= (uint32_t)zp[e] << (16 * (e & 1));
+                        }
+                    }
+                });
+            }
+            stage_half(half);
+            if (dgelu) {
+                static_for<NIT>([&](auto it) {
+                    const floatx4 v = *staged(it);
+                    const int row = wrow0 + it * RPI + elane / CPR;
+                    if (row < g.M && col < g.N) emit4<MODE_BF16_DGELU>(g, row, col, v, bias4, vec, zr[it]);
+                });
+            } else {
+                with_mode([&](auto mode) {
+#pragma unroll 4
+                    for (int it = 0; it < NIT; ++it) {
+                        const floatx4 v = *staged(it);
+                        const int row = wrow0 + it * RPI + elane / CPR;
+                        if (row < g.M && col < g.N) emit4<mode>(g, row, col, v, bias4, vec);
+                    }
+                });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
 #ifdef TESS_STAMPS
-        wait_vmcnt<0>(); TESS_STAMP(4 + 4 * seg);
+        wait_vmcnt<0>(); TESS_STAMP(4);
 #endif
-        if (!streamk) break;
-        lds_barrier();                                 // the next segment's loads overwrite the LDS
     }
 }
 
@@ -1202,12 +993,12 @@ __global__ __launch_bounds__(256) void tess_splitk_reduce_kernel(GemmArgs g)
 }
 
 template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool A_KC, bool B_KC, bool DIRECT,
-          bool COLSUM = false, bool STREAMK = false>
+          bool COLSUM = false>
 static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
-    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT, COLSUM, STREAMK>;
+    auto kern = tess_mfma_kernel<BM, BN, BK, NSTAGE, WGM, WGN, A_KC, B_KC, DIRECT, COLSUM>;
     // the dynamic LDS limit is a per-device attribute of the kernel: set it once per device
     // (a bit per device id; setting it twice from two threads is harmless)
     static std::atomic<uint64_t> attr_done{0};
@@ -1223,11 +1014,6 @@ static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
     const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     GemmArgs a = g;
     a.splits = p.splits > 1 ? p.splits : 1;
-    if constexpr (STREAMK) {
-        // one workgroup per worker, the fix-up happens inside the kernel
-        hipLaunchKernelGGL(kern, dim3(p.sk_workers, 1, 1), dim3(NT), lds_bytes, s, a);
-        return hipGetLastError();
-    }
     hipLaunchKernelGGL(kern, dim3(tiles, 1, a.splits), dim3(NT), lds_bytes, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -1240,14 +1026,14 @@ static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
     return e;
 }
 
-template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool DIRECT, bool STREAMK = false>
+template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, bool DIRECT>
 static hipError_t launch_layout(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
-    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, false, DIRECT, false, STREAMK>(g, p, s);
-    if (g.a_kc && g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, true, DIRECT, false, STREAMK>(g, p, s);
+    if (g.a_kc && !g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, false, DIRECT>(g, p, s);
+    if (g.a_kc && g.b_kc) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, true, true, DIRECT>(g, p, s);
     if (!g.a_kc && !g.b_kc) {
-        if (g.colsum) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT, true, STREAMK>(g, p, s);
-        return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT, false, STREAMK>(g, p, s);
+        if (g.colsum) return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT, true>(g, p, s);
+        return launch_one<BM, BN, BK, NSTAGE, WGM, WGN, false, false, DIRECT>(g, p, s);
     }
     return hipErrorInvalidValue;
 }
@@ -1301,10 +1087,8 @@ hipError_t launch_mfma(const GemmArgs& g, const Plan& p, hipStream_t s)
 {
     if (p.bm == 256 && p.bn == 256) {
         if (!p.direct) return hipErrorInvalidValue;
-        if (p.sk_workers > 0) return launch_layout<256, 256, 64, 2, 2, 2, true, true>(g, p, s);
         return launch_layout<256, 256, 64, 2, 2, 2, true>(g, p, s);
     }
-    if (p.sk_workers > 0) return hipErrorInvalidValue;     // stream-K exists for 256 x 256 tiles only
     if (p.bm == 128 && p.bn == 128) {
         if (!p.direct) return launch_layout<128, 128, 64, 2, 2, 2, false>(g, p, s);
         return launch_layout<128, 128, 64, 3, 2, 2, true>(g, p, s);

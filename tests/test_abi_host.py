@@ -137,7 +137,7 @@ def test_plan_override_is_explicit_and_reversible():
         with pytest.raises(B.TessError):
             B.set_plan_override(tile=64)
     finally:
-        B.set_plan_override(0, 0, -1)
+        B.set_plan_override(0, 0)
     assert B.plan(d, B.OP_BWD_DX) == base
     # the environment no longer steers the product path
     os.environ["TESS_SPLITS"] = "7"

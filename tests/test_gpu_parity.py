@@ -67,6 +67,8 @@ FORCED = [
     (256, 2, (2, 2, 1024, 1024, 1024)),    # 256 x 256 tiles, K split, several tiles
     (256, 1, (2, 2, 1024, 1024, 1024)),
     (256, 3, (2, 1, 576, 320, 832)),       # ragged M and N edges on 256 x 256 tiles, uneven split
+    (256, 5, (4, 1, 512, 512, 768)),       # five parts
+    (256, 8, (4, 1, 512, 512, 512)),
 ]
 
 
@@ -75,13 +77,13 @@ def test_forced_launch_shapes_are_bit_exact(tile, splits, shape):
     q, d, m, kb, n = shape
     inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=17, integers=True)
     try:
-        B.set_plan_override(tile=tile, k_splits=splits, stream_k=0)
+        B.set_plan_override(tile=tile, k_splits=splits)
         desc = B.make_desc(q, d, 0, 0, 0, m * q * d, kb * q, n * q, B.BF16, B.F32)
         for op in (B.OP_FWD, B.OP_BWD_DX, B.OP_BWD_DW):
             assert tess.plan(desc, op) == (tile, tile, splits)
         got = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "f32", act="none")
     finally:
-        B.set_plan_override(0, 0, -1)
+        B.set_plan_override(0, 0)
     want = oracle_share(inp["x"], inp["w"], inp["bias"], inp["dy"], act="none")
     for key in ("y", "dx", "dw"):
         assert np.array_equal(f64(got[key]), want[key]), key
@@ -126,12 +128,12 @@ def test_bf16_gelu_output_does_not_depend_on_asking_for_the_preactivation(tile, 
     q, d, m, kb, n = 2, 2, 512, 256, 768
     inp = wl.share_inputs(q, m, kb, n, dtype="bf16", seed=21, w_std=0.1, bias_std=0.5)
     try:
-        B.set_plan_override(tile=tile, k_splits=splits, stream_k=0)
+        B.set_plan_override(tile=tile, k_splits=splits)
         a = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "bf16", act="gelu_erf")
         b = run_share(q, d, inp["x"], inp["w"], inp["bias"], inp["dy"], "bf16", "bf16", act="gelu_erf",
                       want_preact=True)
     finally:
-        B.set_plan_override(0, 0, -1)
+        B.set_plan_override(0, 0)
     assert torch.equal(a["y"], b["y"])
     z = orc.fwd_panels([f64(inp["x"][t]) for t in range(q)], [f64(inp["w"][t]) for t in range(q)],
                        bias=f64(inp["bias"]), act=orc.ACT_NONE)

@@ -41,7 +41,7 @@ GRIDS = [
 def test_whole_output_is_bit_exact_at_the_real_tile_grid(op, q, M, N, splits):
     gen = torch.Generator().manual_seed(1000 + M + N + splits)
     try:
-        B.set_plan_override(tile=256, k_splits=splits, stream_k=0)
+        B.set_plan_override(tile=256, k_splits=splits)
         if op == "fwd":
             m, kb, n = M, DEPTH, N
             a = _ints((q, m, kb), gen); b = _ints((q, kb, n), gen)
@@ -68,7 +68,7 @@ def test_whole_output_is_bit_exact_at_the_real_tile_grid(op, q, M, N, splits):
             tess.linear_bwd_dw(desc, list(ad), list(bd), out, accumulate=False, workspace=ws)
         torch.cuda.synchronize()
     finally:
-        B.set_plan_override(0, 0, -1)
+        B.set_plan_override(0, 0)
     ap = [f64(a[t]) for t in range(q)]
     bp = [f64(b[t]) for t in range(q)]
     want = {"fwd": orc.fwd_panels, "dx": orc.bwd_dx_panels, "dw": orc.bwd_dw_panels}[op](ap, bp)

@@ -36,12 +36,12 @@ def test_gpu_suite_reaches_every_kernel_variant():
             seen.setdefault(v, ("test_gpu_configs.CASES", (wname, lname)))
     try:
         for tile, splits, (q, d, m, kb, n) in test_gpu_parity.FORCED:
-            B.set_plan_override(tile=tile, k_splits=splits, stream_k=0)
+            B.set_plan_override(tile=tile, k_splits=splits)
             for v in _variants(q, d, m, kb, n):
                 assert v[0][0] == tile and (v[1] == "split") == (splits > 1)
                 seen.setdefault(v, ("test_gpu_parity.FORCED", (tile, splits, q, d, m, kb, n)))
     finally:
-        B.set_plan_override(0, 0, -1)
+        B.set_plan_override(0, 0)
     want = set(itertools.product([(256, "direct"), (128, "direct"), (128, "staged")], ["whole", "split"],
                                  ["fwd", "dx", "dw"]))
     missing = sorted(want - set(seen))
