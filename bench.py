@@ -49,6 +49,10 @@ def parse():
                          "dependent chain (pre-activation kept, GELU' and bias gradients fused)")
     ap.add_argument("--epilogues", action="store_true",
                     help="also time dX through GELU' and dW with the bias gradient beside the plain calls")
+    ap.add_argument("--compare-vendor", action="store_true",
+                    help="diagnostic only: launch this library's input-gradient kernel (q = 1) and the vendor GEMM "
+                         "behind torch.matmul on the same 8192^3 NT problem, a few times each, and print both "
+                         "timings; meant to be run under rocprofv3 counters")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -362,6 +366,35 @@ def main():
         print(json.dumps({"calibrate_copy_bytes": n, "launches": 3}))
         return
     tess.binding.lib()   # fail loudly when the HIP library is missing
+    if args.compare_vendor:
+        # C[M,N] = A[M,K] B[N,K]^T, both operands K-contiguous: the input-gradient orientation
+        M = N = K = 8192
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(0)
+        a = torch.randn((M, K), generator=g, device="cuda:0").to(torch.bfloat16)
+        b = (torch.randn((N, K), generator=g, device="cuda:0") * 0.02).to(torch.bfloat16)
+        desc = B.make_desc(1, 1, 0, 0, 0, M, N, K, B.BF16, B.BF16)      # dX[m, kb] = dY[m, n] W[kb, n]^T
+        out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
+        nbytes = tess.workspace_bytes(desc, B.OP_BWD_DX)
+        ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device="cuda:0")
+        res = {}
+        for name, fn in (("tess_linear_bwd_dx", lambda: tess.linear_bwd_dx(desc, [a], [b], out, workspace=ws)),
+                         ("torch.matmul", lambda: torch.matmul(a, b.t()))):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(6):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 6
+            res[name] = {"ms": round(ms, 4), "tflops": round(2.0 * M * N * K / ms / 1e9, 1)}
+        ref = torch.matmul(a, b.t())
+        res["max_abs_difference"] = float((out.float() - ref.float()).abs().max())
+        print(json.dumps({"compare_vendor": res, "MxNxK": f"{M}x{N}x{K}", "layout": "NT", "dtype": "bf16"}))
+        return
     w = wl.workload_by_name(args.workload)
     if w is None or w.dtype != "bf16":
         print(f"unknown bf16 workload {args.workload}", file=sys.stderr)
