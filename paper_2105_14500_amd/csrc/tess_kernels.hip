@@ -143,15 +143,18 @@ __device__ __forceinline__ void store_out(const GemmArgs& g, int row, int col, f
 }
 
 // ---------------------------------------------------------------------------
-// generic kernel: 64 x 64 output tile per 256 threads, 4 x 4 outputs per thread,
-// any shape, strides and alignment; inputs fp32 or bf16; fp32 FMA, contracted
-// index ascending within a panel and panels in ascending step order.
+// generic kernel: GT x GT output tile (64 or 32) per 256 threads, (GT/16)^2 outputs per
+// thread, any shape, strides and alignment; inputs fp32 or bf16; fp32 FMA, contracted
+// index ascending within a panel and panels in ascending step order.  With few waves per
+// compute unit the loop runs at the latency of its dependent chain, so small problems take
+// the 32 x 32 tile: four times the workgroups, a quarter of the chain per thread.
 // ---------------------------------------------------------------------------
-constexpr int GT = 64;   // tile edge
-constexpr int GK = 16;   // K step
+constexpr int GK = 64;   // K step
 
+template <int GT>
 __global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
 {
+    constexpr int R = GT / 16;          // outputs per thread along each side
     __shared__ float As[GK][GT + 4];
     __shared__ float Bs[GK][GT + 4];
     const int tid = threadIdx.x;
@@ -161,7 +164,7 @@ __global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
     const int64_t a_rs = g.a_kc ? g.lda : 1, a_ks = g.a_kc ? 1 : g.lda;
     // element (kk, col) of the B operand: b_kc ? [col*ldb + kk] : [kk*ldb + col]
     const int64_t b_cs = g.b_kc ? g.ldb : 1, b_ks = g.b_kc ? 1 : g.ldb;
-    float acc[4][4] = {};
+    float acc[R][R] = {};
     // column sums of the B operand: the first tile row, one thread per column
     const bool cs_thread = g.colsum && blockIdx.y == 0 && tid < GT;
     float cs = 0.0f;
@@ -187,13 +190,13 @@ __global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
             }
 #pragma unroll
             for (int kk = 0; kk < GK; ++kk) {
-                float av[4], bv[4];
+                float av[R], bv[R];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) { av[x] = As[kk][ty * 4 + x]; bv[x] = Bs[kk][tx * 4 + x]; }
+                for (int x = 0; x < R; ++x) { av[x] = As[kk][ty * R + x]; bv[x] = Bs[kk][tx * R + x]; }
 #pragma unroll
-                for (int x = 0; x < 4; ++x)
+                for (int x = 0; x < R; ++x)
 #pragma unroll
-                    for (int y = 0; y < 4; ++y) acc[x][y] = fmaf(av[x], bv[y], acc[x][y]);
+                    for (int y = 0; y < R; ++y) acc[x][y] = fmaf(av[x], bv[y], acc[x][y]);
             }
             __syncthreads();
         }
@@ -201,12 +204,12 @@ __global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
     if (cs_thread && col0 + tid < g.N)
         g.colsum[col0 + tid] = g.accumulate ? g.colsum[col0 + tid] + cs : cs;
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        const int row = row0 + ty * 4 + x;
+    for (int x = 0; x < R; ++x) {
+        const int row = row0 + ty * R + x;
         if (row >= g.M) continue;
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            const int col = col0 + tx * 4 + y;
+        for (int y = 0; y < R; ++y) {
+            const int col = col0 + tx * R + y;
             if (col >= g.N) continue;
             const float bv = g.bias ? load_in(g.bias, col, g.in_f32) : 0.0f;
             store_out(g, row, col, acc[x][y], bv);
@@ -216,8 +219,14 @@ __global__ __launch_bounds__(256) void tess_generic_kernel(GemmArgs g)
 
 hipError_t launch_generic(const GemmArgs& g, hipStream_t s)
 {
-    dim3 grid((g.N + GT - 1) / GT, (g.M + GT - 1) / GT, 1);
-    hipLaunchKernelGGL(tess_generic_kernel, grid, dim3(256), 0, s, g);
+    const int64_t tiles64 = (int64_t)((g.N + 63) / 64) * ((g.M + 63) / 64);
+    if (tiles64 < 128) {
+        dim3 grid((g.N + 31) / 32, (g.M + 31) / 32, 1);
+        hipLaunchKernelGGL(tess_generic_kernel<32>, grid, dim3(256), 0, s, g);
+    } else {
+        dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, 1);
+        hipLaunchKernelGGL(tess_generic_kernel<64>, grid, dim3(256), 0, s, g);
+    }
     return hipGetLastError();
 }
 
