@@ -25,7 +25,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define TESS_STAMP(i)                                                                      \
     do {                                                                                   \
         if (threadIdx.x == 0)                                                              \
-            g.stamps[(blockIdx.z * gridDim.x + blockIdx.x) * 16 + (i)] = wall_clock64(); \
+            g.stamps[blockIdx.x * 16 + (i)] = wall_clock64(); \
     } while (0)
 #else
 #define TESS_STAMP(i)
@@ -556,8 +556,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     const int kt_total = g.q * kt_per_panel;
 
     // ---- work of this workgroup: one output tile and a range of K stages: the whole K
-    // loop, or one of g.splits equal parts of it (over gridDim.z, with the reduction kernel
-    // behind the launch)
+    // loop, or one of g.splits equal parts of it (tiles x parts workgroups, with the
+    // reduction kernel behind the launch)
     int tm = 0, tn = 0, row0 = 0, col0 = 0, kt_begin = 0, nkt = 0;
 
     typedef DmaLoader<BM, BK, A_KC, NT> LA;
@@ -699,12 +699,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
 
+    int z = 0;                      // K part of this workgroup
     {
-        tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
         kt_begin = 0;
         nkt = kt_total;
-        if (g.splits > 1) {
-            const int z = blockIdx.z;
+        if (g.splits <= 1) {
+            tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
+        } else {
+            // One launch of tiles x parts workgroups.  In the XCD-major order of the blocks the
+            // parts come one after the other, each with all its tiles: an XCD then works on a
+            // run of tiles of ONE part at a time (the workgroups that share panels in its L2 are
+            // at the same K offset), in patches like the launch without a split.
+            const int v = xcd_major_index(blockIdx.x, gridDim.x);
+            z = v / nb;
+            const int per = (int)(gridDim.x >> 3);
+            tile_of_index(v - z * nb, tiles_m, tiles_n, per >= 32 ? 32 : (per >= 1 ? per : 1), tm, tn);
             const int base = kt_total / g.splits, extra = kt_total % g.splits;
             kt_begin = z * base + (z < extra ? z : extra);
             nkt = base + (z < extra ? 1 : 0);
@@ -806,18 +815,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
             static_for<FN>([&](auto j) { csv[j] = cs[j] + __shfl_xor(cs[j], 32, 64); });
         }
         if (g.splits > 1) {
-            // equal K parts over gridDim.z: partial sums in accumulator order
+            // equal K parts: partial sums in accumulator order
             // [(z*nb + tile)][wave][frag][reg][lane] for the reduction kernel
             if constexpr (COLSUM) {
                 if (cs_wave) {
-                    float* part = g.ws + (size_t)g.splits * nb * (BM * BN) + (size_t)blockIdx.z * g.N;
+                    float* part = g.ws + (size_t)g.splits * nb * (BM * BN) + (size_t)z * g.N;
                     static_for<FN>([&](auto j) {
                         const int col = col0 + ewn * WTN + j * 32 + elane;
                         if (elane < 32 && col < g.N) part[col] = csv[j];
                     });
                 }
             }
-            float* w = g.ws + ((size_t)blockIdx.z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
+            float* w = g.ws + ((size_t)z * nb + (size_t)(tm * tiles_n + tn)) * (BM * BN) +
                        (size_t)ewave * (FM * FN * 16 * 64) + elane;
             static_for<FM * FN>([&](auto f) {
                 static_for<16>([&](auto r) { w[(f * 16 + r) * 64] = acc[f][r()]; });
@@ -1023,7 +1032,7 @@ static hipError_t launch_one(const GemmArgs& g, const Plan& p, hipStream_t s)
     const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     GemmArgs a = g;
     a.splits = p.splits > 1 ? p.splits : 1;
-    hipLaunchKernelGGL(kern, dim3(tiles, 1, a.splits), dim3(NT), lds_bytes, s, a);
+    hipLaunchKernelGGL(kern, dim3(tiles * a.splits, 1, 1), dim3(NT), lds_bytes, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.splits > 1) {
