@@ -525,6 +525,34 @@ __device__ __forceinline__ void emit4(const GemmArgs& g, int row, int col, float
     }
 }
 
+// Eight adjacent columns of one output row in one of the 2-byte output modes: the same
+// arithmetic as two emit4 calls, but the row leaves as one 16-byte store per lane (and the
+// pre-activation as another) when all eight columns exist and the rows are 16-byte aligned.
+template <int MODE>
+__device__ __forceinline__ void emit8_bf16(const GemmArgs& g, int row, int col, floatx4 v0, floatx4 v1,
+                                           floatx4 b0, floatx4 b1, bool vec)
+{
+    static_assert(MODE == MODE_BF16 || MODE == MODE_BF16_GELU || MODE == MODE_BF16_GELU_PRE, "2-byte outputs");
+    if (!(vec && col + 8 <= g.N)) {
+        emit4<MODE>(g, row, col, v0, b0, vec);
+        if (col + 4 < g.N) emit4<MODE>(g, row, col + 4, v1, b1, vec);
+        return;
+    }
+    v0 += b0;
+    v1 += b1;
+    const int64_t o = (int64_t)row * g.ldo + col;
+    if (MODE == MODE_BF16_GELU_PRE) {
+        const u32x2 p0 = pack_bf16x4(v0), p1 = pack_bf16x4(v1);
+        __builtin_nontemporal_store(u32x4{p0[0], p0[1], p1[0], p1[1]}, (u32x4*)((uint16_t*)g.preact + o));
+    }
+    if (MODE != MODE_BF16) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v0[e] = gelu_erf_fast(v0[e]); v1[e] = gelu_erf_fast(v1[e]); }
+    }
+    const u32x2 w0 = pack_bf16x4(v0), w1 = pack_bf16x4(v1);
+    __builtin_nontemporal_store(u32x4{w0[0], w0[1], w1[0], w1[1]}, (u32x4*)((uint16_t*)g.out + o));
+}
+
 // WGM x WGN wavefronts tile the BM x BN macro tile; each owns (BM/WGM) x (BN/WGN).
 // COLSUM: the wavefronts in the first tile row that hold the top wave tile also sum the
 // columns of the B operand over the contraction, from the B fragments they already hold
@@ -937,11 +965,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
                 });
             } else {
                 with_mode([&](auto mode) {
+                    if constexpr (mode == MODE_BF16 || mode == MODE_BF16_GELU || mode == MODE_BF16_GELU_PRE) {
+                        // 2-byte outputs: eight columns per lane, so that a row leaves in 16-byte stores
+                        constexpr int CPR8 = WTN / 8, RPI8 = 64 / CPR8, NIT8 = HR / RPI8;
+                        const int c8 = elane % CPR8, col8 = wcol0 + c8 * 8;
+                        floatx4 b0 = {0.f, 0.f, 0.f, 0.f}, b1 = {0.f, 0.f, 0.f, 0.f};
+                        if (g.bias) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                if (col8 + e < g.N) b0[e] = bf16_bits_to_f32(((const uint16_t*)g.bias)[col8 + e]);
+                                if (col8 + 4 + e < g.N) b1[e] = bf16_bits_to_f32(((const uint16_t*)g.bias)[col8 + 4 + e]);
+                            }
+                        }
 #pragma unroll 4
-                    for (int it = 0; it < NIT; ++it) {
-                        const floatx4 v = *staged(it);
-                        const int row = wrow0 + it * RPI + elane / CPR;
-                        if (row < g.M && col < g.N) emit4<mode>(g, row, col, v, bias4, vec);
+                        for (int it = 0; it < NIT8; ++it) {
+                            const int rl = it * RPI8 + elane / CPR8;
+                            const int sw = ((rl >> 2) & 1) << 3;
+                            const floatx4 v0 = *(const floatx4*)(slice + rl * ROWB + ((2 * c8) ^ sw) * 16);
+                            const floatx4 v1 = *(const floatx4*)(slice + rl * ROWB + ((2 * c8 + 1) ^ sw) * 16);
+                            const int row = wrow0 + rl;
+                            if (row < g.M && col8 < g.N) emit8_bf16<mode>(g, row, col8, v0, v1, b0, b1, vec);
+                        }
+                    } else {
+#pragma unroll 4
+                        for (int it = 0; it < NIT; ++it) {
+                            const floatx4 v = *staged(it);
+                            const int row = wrow0 + it * RPI + elane / CPR;
+                            if (row < g.M && col < g.N) emit4<mode>(g, row, col, v, bias4, vec);
+                        }
                     }
                 });
             }
