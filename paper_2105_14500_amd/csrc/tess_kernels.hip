@@ -681,7 +681,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
         rq_asoff = __builtin_amdgcn_readfirstlane(ld_ks * a_kstep);
         rq_bsoff = __builtin_amdgcn_readfirstlane(ld_ks * b_kstep);
 #ifdef TESS_DBG_SAMEK
-        rq_asoff = rq_bsoff = 0;
+        rq_asoff = rq_bsoff = 0;      // diagnostic build (wrong results): every stage re-reads K slice 0, so all requests hit the L2
 #endif
         const int t = ld_t < g.q ? ld_t : g.q - 1;
         rq_rsrc_a = LA::descriptor(ka->a[t]);
@@ -697,7 +697,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tess_mfma_kernel(GemmArgs g)
     constexpr int STRIDE = RQ_SPAN / LOADS;
     static_assert(STRIDE >= 1, "requests spaced evenly over the MFMA slots");
     auto request_at = [&](auto slot) {
-#ifndef TESS_DBG_NOLOAD
+#ifndef TESS_DBG_NOLOAD   // (a diagnostic build without the in-loop requests measures the loop on resident data)
         if constexpr (slot % STRIDE == 0 && slot / STRIDE < LOADS)
             request(std::integral_constant<int, slot / STRIDE>{});
 #endif
