@@ -405,7 +405,7 @@ struct FragReader {
     uint32_t kcol[KC ? KSTEPS : 2];   // KC: byte offset of the k-chunk for each k16 step
     __device__ __forceinline__ void init(int lane, int wave_origin)
     {
-        if (KC) {
+        if constexpr (KC) {
             const int r = wave_origin + (lane & 31);
             lane_off = (uint32_t)r * (uint32_t)(BK * 2);
             static_for<KSTEPS>([&](auto kk) {
@@ -422,7 +422,7 @@ struct FragReader {
     // f: fragment index along R inside the wave tile, kk: k16 step of the stage
     __device__ __forceinline__ bf16x8 read(const char* lds_tile, int f, int kk) const
     {
-        if (KC) {
+        if constexpr (KC) {
             return *(const bf16x8*)(lds_tile + lane_off + f * (32 * BK * 2) + kcol[kk]);
         } else {
             const uint32_t gsw = ((kcol[1] + 4u * f) ^ kcol[0]) * 16u;
